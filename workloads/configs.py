@@ -1,0 +1,68 @@
+"""Shape descriptors of the synthetic workloads.
+
+The paper trains image classifiers (ResNet/VGG families on CIFAR-size images)
+and text models (Sec. 4.1); it never prints layer shapes, so the descriptors
+below are stand-ins of the same kind: two multilayer perceptrons, a basic-block
+and a bottleneck residual CNN, and a pre-LayerNorm Transformer encoder.  Only
+shapes live here.
+
+A model is a list of *units*; the backward pass may stop only between units
+(the paper's "fraction of the layers from the end", Sec. 1 and Sec. 2).
+Depth k counts units from the output end.
+"""
+from __future__ import annotations
+
+import copy
+
+CONFIGS = {
+    # Linear 784->256->256->256->10, ReLU between, softmax cross-entropy.
+    "cfg1": dict(family="mlp", dtype="f32", batch=64,
+                 dims=[784, 256, 256, 256, 10], depths=[2]),
+    # 8 Linear layers of width 1024, 100 classes.
+    "cfg2": dict(family="mlp", dtype="bf16", batch=256,
+                 dims=[1024] * 8 + [100], depths=[1, 2, 3, 4, 5, 6, 7, 8]),
+    # ResNet-18-style, CIFAR-size input; units = stem | 8 basic blocks | head.
+    "cfg3": dict(family="resnet_basic", dtype="bf16", batch=128,
+                 image=[32, 32, 3], stem=dict(kernel=3, stride=1, pad=1, pool=False, width=64),
+                 stage_blocks=[2, 2, 2, 2], stage_widths=[64, 128, 256, 512],
+                 classes=10, depths=[3, 5, 7, 9]),
+    # ResNet-50-style; units = stem | 16 bottlenecks | head.
+    "cfg4": dict(family="resnet_bottleneck", dtype="bf16", batch=64,
+                 image=[224, 224, 3], stem=dict(kernel=7, stride=2, pad=3, pool=True, width=64),
+                 stage_blocks=[3, 4, 6, 3], stage_widths=[256, 512, 1024, 2048],
+                 classes=1000, depths=[4, 10, 14, 17]),
+    # BERT-base-shaped pre-LN encoder; units = embedding | 12 layers | head.
+    "cfg5": dict(family="encoder", dtype="bf16", batch=32, seq=128, layers=12,
+                 hidden=768, heads=12, ffn=3072, vocab=30522, loss_rows=614,
+                 depths=[4, 7, 13]),
+    # Small relatives used by the CPU tests and the small parity cases.
+    "tiny_mlp_f32": dict(family="mlp", dtype="f32", batch=5,
+                         dims=[12, 8, 8, 4], depths=[0, 1, 2, 3]),
+    "ragged_mlp_f32": dict(family="mlp", dtype="f32", batch=37,
+                           dims=[100, 72, 136, 52, 7], depths=[0, 1, 2, 3, 4]),
+    "ragged_mlp_bf16": dict(family="mlp", dtype="bf16", batch=83,
+                            dims=[136, 200, 72, 264, 13], depths=[0, 1, 2, 3, 4]),
+    "one_layer_bf16": dict(family="mlp", dtype="bf16", batch=16,
+                           dims=[64, 10], depths=[0, 1]),
+}
+
+
+def get_config(name: str) -> dict:
+    cfg = copy.deepcopy(CONFIGS[name])
+    cfg["name"] = name
+    return cfg
+
+
+def unit_count(cfg: dict) -> int:
+    fam = cfg["family"]
+    if fam == "mlp":
+        return len(cfg["dims"]) - 1
+    if fam in ("resnet_basic", "resnet_bottleneck"):
+        return 1 + sum(cfg["stage_blocks"]) + 1
+    if fam == "encoder":
+        return 1 + cfg["layers"] + 1
+    raise ValueError(fam)
+
+
+def depth_sweep(cfg: dict) -> list:
+    return list(cfg["depths"])

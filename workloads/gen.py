@@ -1,0 +1,74 @@
+"""Seeded tensor generators.
+
+Every tensor is drawn from its own counter-based stream (numpy's Philox keyed
+by the seed and a hash of the tensor's name), in float64, and rounded once to
+the workload's storage type.  Consumers on both sides start from the rounded
+values.
+"""
+from __future__ import annotations
+
+import zlib
+
+import numpy as np
+import torch
+
+_TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def _stream(seed: int, name: str) -> np.random.Generator:
+    key = (int(seed) & 0xFFFFFFFF) | (zlib.crc32(name.encode()) << 32)
+    return np.random.Generator(np.random.Philox(key=key))
+
+
+def _normal(seed, name, shape, std):
+    return _stream(seed, name).standard_normal(size=shape) * std
+
+
+def _store(arr: np.ndarray, dtype: str) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(arr)).to(_TORCH_DTYPE[dtype])
+
+
+def tensor_specs(cfg: dict) -> list:
+    """[(name, shape, unit, init)] in unit order, input end first.
+
+    init: ("normal", std) | ("const", value)
+    """
+    fam = cfg["family"]
+    specs = []
+    if fam == "mlp":
+        dims = cfg["dims"]
+        for i in range(len(dims) - 1):
+            fan_in = dims[i]
+            specs.append((f"fc{i}.weight", (dims[i + 1], dims[i]), i, ("normal", (2.0 / fan_in) ** 0.5)))
+            specs.append((f"fc{i}.bias", (dims[i + 1],), i, ("const", 0.0)))
+        return specs
+    raise NotImplementedError(fam)
+
+
+def make_params(cfg: dict, seed: int = 0, perturbed: bool = False) -> dict:
+    """name -> CPU tensor in the workload's storage type.
+
+    perturbed=True replaces the constant initial values (zero biases and
+    shifts, unit scales) by values with a N(0, 0.1^2) spread, so that a missing
+    bias add or scale cannot hide behind a neutral element.
+    """
+    out = {}
+    for name, shape, _unit, init in tensor_specs(cfg):
+        if init[0] == "normal":
+            arr = _normal(seed, name, shape, init[1])
+        else:
+            arr = np.full(shape, init[1], dtype=np.float64)
+            if perturbed:
+                arr = arr + _normal(seed, name + "/perturb", shape, 0.1)
+        out[name] = _store(arr, cfg["dtype"])
+    return out
+
+
+def make_batch(cfg: dict, seed: int = 0) -> dict:
+    fam = cfg["family"]
+    if fam == "mlp":
+        b, d, c = cfg["batch"], cfg["dims"][0], cfg["dims"][-1]
+        x = _store(_normal(seed, "batch/x", (b, d), 1.0), cfg["dtype"])
+        labels = _stream(seed, "batch/labels").integers(0, c, size=(b,), dtype=np.int32)
+        return {"x": x, "labels": torch.from_numpy(labels)}
+    raise NotImplementedError(fam)
