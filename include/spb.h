@@ -1,0 +1,181 @@
+/*
+ * spb.h - C ABI of the Structured Partial Backpropagation (SPB) worker step.
+ *
+ * One worker's training step as the paper states it (Sec. 2): run the complete
+ * forward pass to the loss, then backpropagate over a fixed suffix of the
+ * network, starting at the output layer, and hand over the gradients of that
+ * suffix only.  Layers below the cut get no input gradient, no weight gradient
+ * and no saved activation (Sec. 1: "avoid storing intermediate outputs for
+ * layers that are not going to participate in the backward pass").
+ *
+ * A model is an ordered list of units; the backward pass may stop only between
+ * units.  L = number of units.  Depth k = number of units, counted from the
+ * output end, that are backpropagated: k = 0 computes no gradient, k = L is
+ * ordinary backpropagation.
+ *
+ * Conventions
+ *   - Every call returns 0 (SPB_OK) or a negative error code; spb_last_error()
+ *     gives the message of the calling thread's last failure.  Argument errors
+ *     are found on the host before anything is enqueued.
+ *   - The library allocates no device memory.  Parameters, gradient buffers,
+ *     inputs, labels and one workspace are DEVICE pointers owned by the caller
+ *     and must stay alive until the stream work that uses them has completed.
+ *     Parameters stay resident on the device between calls (cf. Sec. 3, keeping
+ *     model parameters in GPU memory across task switches).
+ *   - Work is enqueued on the caller's stream (a hipStream_t passed as void*);
+ *     calls return without waiting for the device and may be captured into a
+ *     HIP graph.  Calls on one model must not overlap in time.
+ *   - All matrices are row-major.  Activations of perceptrons are
+ *     [batch, features].
+ *   - A model needs a GPU; there is no host fallback.
+ */
+#ifndef SPB_H
+#define SPB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPB_OK 0
+#define SPB_ERR_INVALID_ARG (-1) /* null pointer, bad shape, misaligned buffer */
+#define SPB_ERR_DEPTH_RANGE (-2) /* k < 0 or k > L */
+#define SPB_ERR_STATE (-3)       /* backward without forward, or deeper than the forward stashed for */
+#define SPB_ERR_WORKSPACE (-4)   /* workspace too small or misaligned */
+#define SPB_ERR_HIP (-5)         /* the HIP runtime refused a launch */
+#define SPB_ERR_UNSUPPORTED (-6) /* model family not built into this library */
+
+#define SPB_FAMILY_MLP 0               /* Linear(+ReLU) units, softmax cross-entropy on the last */
+#define SPB_FAMILY_RESNET_BASIC 1      /* stem | basic residual blocks | pooled classifier */
+#define SPB_FAMILY_RESNET_BOTTLENECK 2 /* stem | bottleneck residual blocks | pooled classifier */
+#define SPB_FAMILY_ENCODER 3           /* embedding | pre-LN Transformer layers | masked-token head */
+
+#define SPB_DTYPE_F32 0
+#define SPB_DTYPE_BF16 1 /* bfloat16 storage, float32 accumulation */
+#define SPB_DTYPE_I32 2
+
+#define SPB_MAX_DIMS 64
+#define SPB_MAX_STAGES 8
+#define SPB_NAME_LEN 48
+
+typedef struct spb_model spb_model;
+
+/* Shape of a model.  Only the fields of the chosen family are read. */
+typedef struct spb_model_desc {
+  int32_t family; /* SPB_FAMILY_* */
+  int32_t dtype;  /* SPB_DTYPE_F32 or SPB_DTYPE_BF16: storage type of parameters, inputs, activations */
+  int32_t batch;  /* samples per step */
+  /* MLP: n_dims widths, input first; unit i is Linear dims[i] -> dims[i+1]; ReLU after all but the last */
+  int32_t n_dims;
+  int32_t dims[SPB_MAX_DIMS];
+  /* residual CNNs: NHWC images, stem conv (+ optional 3x3/2 max-pool), stages of blocks, classes */
+  int32_t image_h, image_w, image_c;
+  int32_t stem_kernel, stem_stride, stem_pad, stem_pool, stem_width;
+  int32_t n_stages;
+  int32_t stage_blocks[SPB_MAX_STAGES];
+  int32_t stage_widths[SPB_MAX_STAGES];
+  int32_t classes;
+  /* encoder */
+  int32_t seq, layers, hidden, heads, ffn, vocab, loss_rows;
+} spb_model_desc;
+
+/* One parameter tensor of a model. */
+typedef struct spb_tensor_info {
+  char name[SPB_NAME_LEN]; /* e.g. "fc3.weight" */
+  int32_t unit;            /* owning unit, 0 = input end */
+  int32_t dtype;           /* storage type of the parameter; its gradient is always float32 */
+  int32_t ndim;
+  int64_t shape[4];
+  int64_t numel;
+} spb_tensor_info;
+
+/* One gradient buffer produced by a truncated backward pass. */
+typedef struct spb_grad_view {
+  int32_t param_index; /* index into spb_param_info */
+  int32_t unit;
+  void* data;          /* device pointer, float32, the parameter's shape, dense row-major */
+  int64_t numel;
+} spb_grad_view;
+
+/* Per-kernel timing record (see spb_set_kernel_timing). */
+typedef struct spb_kernel_time {
+  char name[SPB_NAME_LEN]; /* kernel class, e.g. "gemm_bf16_wgrad" */
+  int64_t launches;
+  double total_ms; /* sum of HIP-event durations of those launches */
+  double flops;    /* algorithmic floating-point operations of those launches (2*M*N*K per product) */
+  double bytes;    /* algorithmic bytes: each operand read once, each result written once */
+} spb_kernel_time;
+
+/* Message of the calling thread's most recent failed call ("" if none).  Host pointer, owned by the library. */
+const char* spb_last_error(void);
+
+/* Create the host-side description of a model (unit list, parameter list, buffer plan).
+ * desc: host pointer, copied.  out: receives a handle owned by the library until spb_model_destroy.
+ * Errors: INVALID_ARG (null, non-positive sizes, feature widths that are not a multiple of 16 bytes
+ * except the last), UNSUPPORTED. */
+int spb_model_create(const spb_model_desc* desc, spb_model** out);
+int spb_model_destroy(spb_model* m);
+
+/* L, the number of units (Sec. 2: "a L layer DNN"; here the cut unit of the model). */
+int spb_num_units(const spb_model* m, int32_t* n_units);
+
+/* Parameter list, unit order, input end first. */
+int spb_param_count(const spb_model* m, int32_t* n_params);
+int spb_param_info(const spb_model* m, int32_t index, spb_tensor_info* out);
+
+/* Bind device buffers.  ptrs: host array of n device pointers, n = spb_param_count; entry i holds
+ * parameter i (model dtype, dense row-major) or its gradient buffer (float32, same shape).  Buffers must
+ * be 16-byte aligned.  Gradient entries of parameters that no later call backpropagates may be NULL. */
+int spb_bind_params(spb_model* m, void* const* ptrs, int32_t n);
+int spb_bind_grads(spb_model* m, void* const* ptrs, int32_t n);
+
+/* Bytes of workspace a forward pass that stashes for depth k needs.  Non-decreasing in k: below the
+ * cut only two ping-pong activation buffers exist; above it every activation the top k units'
+ * backward pass reads is kept (Sec. 1, Table 1's peak-memory column).  Errors: DEPTH_RANGE. */
+int spb_workspace_size(const spb_model* m, int32_t k, size_t* bytes);
+
+/* Full forward pass to the loss (Sec. 2: "performs a forward pass to obtain the loss with respect to
+ * the model"), keeping only what a backward pass of depth <= stash_depth_k will read.
+ *   x          device, model dtype: [batch, dims[0]] (MLP), NHWC images (CNN); int32 token ids (encoder)
+ *   labels     device, int32, one class index per loss row, each in [0, classes)
+ *   loss_rows  device, int32 row indices that carry a loss (encoder); NULL otherwise
+ *   workspace  device, 256-byte aligned, >= spb_workspace_size(stash_depth_k) bytes; holds the stash
+ *              until the matching backward call has completed
+ *   loss_out   device, one float32: mean softmax cross-entropy over the loss rows
+ * Errors: INVALID_ARG, DEPTH_RANGE, STATE (parameters not bound), WORKSPACE, HIP. */
+int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_t* loss_rows,
+                int32_t stash_depth_k, void* workspace, size_t workspace_bytes, float* loss_out,
+                void* stream);
+
+/* Backward pass over the top k units only (Sec. 2: "each worker performs backpropagation on a fixed
+ * suffix of the network ... starting from the output layer").  Requires a preceding spb_forward with
+ * stash_depth_k >= k on the same workspace.  Overwrites (does not accumulate into) the gradient
+ * buffers of units >= L-k and touches no other gradient buffer; the lowest visited unit gets its
+ * parameter gradients but no input gradient is formed for it.  k = 0 enqueues nothing.
+ * Errors: DEPTH_RANGE, STATE (no forward, deeper than stashed, gradient buffer of a visited unit
+ * not bound), HIP. */
+int spb_backward_truncated(spb_model* m, int32_t k, void* stream);
+
+/* The gradients a worker sends after a depth-k step (Sec. 2: "each worker sends the gradients
+ * computed"): one view per parameter of the top k units, output end first, and nothing for the
+ * units below the cut.  out: host array of cap entries; n_out receives the count (0 for k = 0).
+ * Errors: DEPTH_RANGE, INVALID_ARG (cap too small), STATE (gradients not bound). */
+int spb_grad_buffers(const spb_model* m, int32_t k, spb_grad_view* out, int32_t cap, int32_t* n_out);
+
+/* Fill with zeros the gradient buffers of the units below the cut, for callers that want dense
+ * gradients ("absent or zero").  Buffers bound as NULL are skipped. */
+int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream);
+
+/* Kernel timing.  When enabled, every kernel the model enqueues is bracketed by two HIP events on
+ * the launch stream.  spb_read_kernel_timing waits for the recorded events, adds them up per kernel
+ * class into out (host array of cap records; n_out receives the count) and clears the record.
+ * Must not be enabled while the stream is being captured into a graph. */
+int spb_set_kernel_timing(spb_model* m, int32_t enable);
+int spb_read_kernel_timing(spb_model* m, spb_kernel_time* out, int32_t cap, int32_t* n_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPB_H */

@@ -1,0 +1,267 @@
+// The C ABI (include/spb.h): argument checks on the host, then the family's step driver.
+#include "model.h"
+
+#include <cstring>
+#include <map>
+
+namespace spb {
+
+static thread_local std::string g_last_error;
+
+void set_error(const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+}
+
+int Model::check(hipError_t e, const char* what) {
+  if (e == hipSuccess) return SPB_OK;
+  if (e == hipErrorInvalidValue) { set_error("%s: shapes or alignment not accepted by the kernel", what); return SPB_ERR_INVALID_ARG; }
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return SPB_ERR_HIP;
+}
+
+int Model::gemm(const GemmProblem& p, hipStream_t s) {
+  hipError_t e = timer.run(p.name, gemm_flops(p), gemm_bytes(p), s, [&] { return launch_gemm(p, s); });
+  return check(e, p.name);
+}
+
+KernelTimer::~KernelTimer() {
+  for (auto& r : recs_) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+  for (auto e : pool_) (void)hipEventDestroy(e);
+}
+
+void KernelTimer::enable(bool on) { enabled_ = on; }
+
+void KernelTimer::get_events(hipEvent_t* a, hipEvent_t* b) {
+  hipEvent_t* out[2] = {a, b};
+  for (auto* o : out) {
+    if (!pool_.empty()) { *o = pool_.back(); pool_.pop_back(); }
+    else (void)hipEventCreate(o);
+  }
+}
+
+hipError_t KernelTimer::run(const char* name, double flops, double bytes, hipStream_t stream, const std::function<hipError_t()>& launch) {
+  if (!enabled_) return launch();
+  Rec r;
+  r.name = name; r.flops = flops; r.bytes = bytes;
+  get_events(&r.start, &r.stop);
+  (void)hipEventRecord(r.start, stream);
+  hipError_t e = launch();
+  (void)hipEventRecord(r.stop, stream);
+  recs_.push_back(r);
+  return e;
+}
+
+int KernelTimer::read(spb_kernel_time* out, int cap, int* n_out) {
+  std::map<std::string, spb_kernel_time> acc;
+  std::vector<std::string> order;
+  for (auto& r : recs_) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess) {
+      set_error("kernel timing: event query failed");
+      return SPB_ERR_HIP;
+    }
+    auto it = acc.find(r.name);
+    if (it == acc.end()) {
+      spb_kernel_time t;
+      std::memset(&t, 0, sizeof t);
+      std::snprintf(t.name, sizeof t.name, "%s", r.name.c_str());
+      it = acc.emplace(r.name, t).first;
+      order.push_back(r.name);
+    }
+    it->second.launches += 1;
+    it->second.total_ms += ms;
+    it->second.flops += r.flops;
+    it->second.bytes += r.bytes;
+  }
+  if ((int)order.size() > cap) { set_error("kernel timing: %zu records, room for %d", order.size(), cap); return SPB_ERR_INVALID_ARG; }
+  for (size_t i = 0; i < order.size(); ++i) out[i] = acc[order[i]];
+  *n_out = (int)order.size();
+  for (auto& r : recs_) { pool_.push_back(r.start); pool_.push_back(r.stop); }
+  recs_.clear();
+  return SPB_OK;
+}
+
+}  // namespace spb
+
+using spb::set_error;
+
+#define SPB_REQUIRE(cond, code, ...) \
+  do { if (!(cond)) { set_error(__VA_ARGS__); return (code); } } while (0)
+
+static int depth_ok(const spb_model* m, int k, const char* who) {
+  if (k < 0 || k > m->impl->num_units) { set_error("%s: depth %d outside 0..%d", who, k, m->impl->num_units); return SPB_ERR_DEPTH_RANGE; }
+  return SPB_OK;
+}
+
+extern "C" {
+
+const char* spb_last_error(void) { return spb::g_last_error.c_str(); }
+
+int spb_model_create(const spb_model_desc* desc, spb_model** out) {
+  SPB_REQUIRE(desc && out, SPB_ERR_INVALID_ARG, "spb_model_create: null argument");
+  *out = nullptr;
+  SPB_REQUIRE(desc->dtype == SPB_DTYPE_F32 || desc->dtype == SPB_DTYPE_BF16, SPB_ERR_INVALID_ARG, "spb_model_create: dtype %d", desc->dtype);
+  SPB_REQUIRE(desc->batch > 0, SPB_ERR_INVALID_ARG, "spb_model_create: batch %d", desc->batch);
+  std::unique_ptr<spb::Model> impl;
+  switch (desc->family) {
+    case SPB_FAMILY_MLP: impl = spb::make_mlp(*desc); break;
+    case SPB_FAMILY_RESNET_BASIC:
+    case SPB_FAMILY_RESNET_BOTTLENECK:
+    case SPB_FAMILY_ENCODER:
+      set_error("spb_model_create: family %d is not built into this library", desc->family);
+      return SPB_ERR_UNSUPPORTED;
+    default:
+      set_error("spb_model_create: unknown family %d", desc->family);
+      return SPB_ERR_INVALID_ARG;
+  }
+  if (!impl) return SPB_ERR_INVALID_ARG;
+  *out = new spb_model{std::move(impl)};
+  return SPB_OK;
+}
+
+int spb_model_destroy(spb_model* m) {
+  SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_model_destroy: null model");
+  delete m;
+  return SPB_OK;
+}
+
+int spb_num_units(const spb_model* m, int32_t* n_units) {
+  SPB_REQUIRE(m && n_units, SPB_ERR_INVALID_ARG, "spb_num_units: null argument");
+  *n_units = m->impl->num_units;
+  return SPB_OK;
+}
+
+int spb_param_count(const spb_model* m, int32_t* n_params) {
+  SPB_REQUIRE(m && n_params, SPB_ERR_INVALID_ARG, "spb_param_count: null argument");
+  *n_params = (int32_t)m->impl->params.size();
+  return SPB_OK;
+}
+
+int spb_param_info(const spb_model* m, int32_t index, spb_tensor_info* out) {
+  SPB_REQUIRE(m && out, SPB_ERR_INVALID_ARG, "spb_param_info: null argument");
+  SPB_REQUIRE(index >= 0 && index < (int)m->impl->params.size(), SPB_ERR_INVALID_ARG, "spb_param_info: index %d outside 0..%zu", index, m->impl->params.size() - 1);
+  const spb::ParamInfo& p = m->impl->params[index];
+  std::memset(out, 0, sizeof *out);
+  std::snprintf(out->name, sizeof out->name, "%s", p.name.c_str());
+  out->unit = p.unit;
+  out->dtype = p.dtype == spb::DType::F32 ? SPB_DTYPE_F32 : SPB_DTYPE_BF16;
+  out->ndim = (int32_t)p.shape.size();
+  for (size_t i = 0; i < p.shape.size() && i < 4; ++i) out->shape[i] = p.shape[i];
+  out->numel = p.numel();
+  return SPB_OK;
+}
+
+static int bind(spb_model* m, void* const* ptrs, int32_t n, bool grads) {
+  const char* who = grads ? "spb_bind_grads" : "spb_bind_params";
+  SPB_REQUIRE(m && ptrs, SPB_ERR_INVALID_ARG, "%s: null argument", who);
+  SPB_REQUIRE(n == (int)m->impl->params.size(), SPB_ERR_INVALID_ARG, "%s: %d pointers for %zu parameters", who, n, m->impl->params.size());
+  for (int i = 0; i < n; ++i) {
+    SPB_REQUIRE(grads || ptrs[i], SPB_ERR_INVALID_ARG, "%s: pointer %d (%s) is null", who, i, m->impl->params[i].name.c_str());
+    SPB_REQUIRE((reinterpret_cast<uintptr_t>(ptrs[i]) & 15u) == 0, SPB_ERR_INVALID_ARG, "%s: pointer %d (%s) is not 16-byte aligned", who, i, m->impl->params[i].name.c_str());
+  }
+  auto& dst = grads ? m->impl->grad_ptrs : m->impl->param_ptrs;
+  dst.assign(ptrs, ptrs + n);
+  (grads ? m->impl->grads_bound : m->impl->params_bound) = true;
+  return SPB_OK;
+}
+
+int spb_bind_params(spb_model* m, void* const* ptrs, int32_t n) { return bind(m, ptrs, n, false); }
+int spb_bind_grads(spb_model* m, void* const* ptrs, int32_t n) { return bind(m, ptrs, n, true); }
+
+int spb_workspace_size(const spb_model* m, int32_t k, size_t* bytes) {
+  SPB_REQUIRE(m && bytes, SPB_ERR_INVALID_ARG, "spb_workspace_size: null argument");
+  if (int rc = depth_ok(m, k, "spb_workspace_size")) return rc;
+  *bytes = m->impl->workspace_size(k);
+  return SPB_OK;
+}
+
+int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_t* loss_rows, int32_t k,
+                void* workspace, size_t workspace_bytes, float* loss_out, void* stream) {
+  SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_forward: null model");
+  m->impl->stashed_k = -1;
+  SPB_REQUIRE(x && labels && loss_out, SPB_ERR_INVALID_ARG, "spb_forward: null input, labels or loss pointer");
+  SPB_REQUIRE((reinterpret_cast<uintptr_t>(x) & 15u) == 0, SPB_ERR_INVALID_ARG, "spb_forward: input is not 16-byte aligned");
+  if (int rc = depth_ok(m, k, "spb_forward")) return rc;
+  SPB_REQUIRE(m->impl->params_bound, SPB_ERR_STATE, "spb_forward: parameters are not bound");
+  const size_t need = m->impl->workspace_size(k);
+  SPB_REQUIRE(workspace && workspace_bytes >= need, SPB_ERR_WORKSPACE, "spb_forward: workspace of %zu bytes, depth %d needs %zu", workspace_bytes, k, need);
+  SPB_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, SPB_ERR_WORKSPACE, "spb_forward: workspace is not 256-byte aligned");
+  int rc = m->impl->forward(x, labels, loss_rows, k, workspace, loss_out, static_cast<hipStream_t>(stream));
+  if (rc != SPB_OK) return rc;
+  m->impl->stashed_k = k;
+  m->impl->ws = workspace;
+  return SPB_OK;
+}
+
+static int grads_ok(const spb_model* m, int k, const char* who) {
+  const auto& im = *m->impl;
+  if (k > 0 && !im.grads_bound) { set_error("%s: gradient buffers are not bound", who); return SPB_ERR_STATE; }
+  for (size_t i = 0; i < im.params.size(); ++i)
+    if (im.params[i].unit >= im.num_units - k && !im.grad_ptrs[i]) {
+      set_error("%s: gradient buffer of %s (unit %d, above the cut at depth %d) is null", who, im.params[i].name.c_str(), im.params[i].unit, k);
+      return SPB_ERR_STATE;
+    }
+  return SPB_OK;
+}
+
+int spb_backward_truncated(spb_model* m, int32_t k, void* stream) {
+  SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_backward_truncated: null model");
+  if (int rc = depth_ok(m, k, "spb_backward_truncated")) return rc;
+  SPB_REQUIRE(m->impl->stashed_k >= 0, SPB_ERR_STATE, "spb_backward_truncated: no forward pass has run");
+  SPB_REQUIRE(k <= m->impl->stashed_k, SPB_ERR_STATE, "spb_backward_truncated: depth %d, but the forward pass stashed for depth %d", k, m->impl->stashed_k);
+  if (k == 0) return SPB_OK;
+  if (int rc = grads_ok(m, k, "spb_backward_truncated")) return rc;
+  return m->impl->backward(k, static_cast<hipStream_t>(stream));
+}
+
+int spb_grad_buffers(const spb_model* m, int32_t k, spb_grad_view* out, int32_t cap, int32_t* n_out) {
+  SPB_REQUIRE(m && n_out, SPB_ERR_INVALID_ARG, "spb_grad_buffers: null argument");
+  if (int rc = depth_ok(m, k, "spb_grad_buffers")) return rc;
+  *n_out = 0;
+  if (k == 0) return SPB_OK;
+  if (int rc = grads_ok(m, k, "spb_grad_buffers")) return rc;
+  const auto& im = *m->impl;
+  int n = 0;
+  for (int u = im.num_units - 1; u >= im.num_units - k; --u)
+    for (size_t i = 0; i < im.params.size(); ++i)
+      if (im.params[i].unit == u) {
+        SPB_REQUIRE(out && n < cap, SPB_ERR_INVALID_ARG, "spb_grad_buffers: room for %d views is not enough at depth %d", cap, k);
+        out[n].param_index = (int32_t)i;
+        out[n].unit = u;
+        out[n].data = im.grad_ptrs[i];
+        out[n].numel = im.params[i].numel();
+        ++n;
+      }
+  *n_out = n;
+  return SPB_OK;
+}
+
+int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream) {
+  SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_zero_absent_grads: null model");
+  if (int rc = depth_ok(m, k, "spb_zero_absent_grads")) return rc;
+  auto& im = *m->impl;
+  for (size_t i = 0; i < im.params.size(); ++i)
+    if (im.params[i].unit < im.num_units - k && im.grad_ptrs[i]) {
+      hipError_t e = spb::launch_fill_zero(im.grad_ptrs[i], (size_t)im.params[i].numel() * 4, static_cast<hipStream_t>(stream));
+      if (e != hipSuccess) { set_error("spb_zero_absent_grads: %s", hipGetErrorString(e)); return SPB_ERR_HIP; }
+    }
+  return SPB_OK;
+}
+
+int spb_set_kernel_timing(spb_model* m, int32_t enable) {
+  SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_set_kernel_timing: null model");
+  m->impl->timer.enable(enable != 0);
+  return SPB_OK;
+}
+
+int spb_read_kernel_timing(spb_model* m, spb_kernel_time* out, int32_t cap, int32_t* n_out) {
+  SPB_REQUIRE(m && out && n_out && cap > 0, SPB_ERR_INVALID_ARG, "spb_read_kernel_timing: null argument");
+  return m->impl->timer.read(out, cap, n_out);
+}
+
+}  // extern "C"

@@ -1,0 +1,118 @@
+// Softmax cross-entropy, forward and gradient in one pass over the logits (the loss that ends the
+// forward pass and starts the backward pass, Sec. 1-2 of the paper).  Memory-bound: every logit is
+// read from HBM once (the row stays in registers or L2 for the second sweep) and every gradient
+// entry is written once.
+#include "kernels.h"
+
+namespace spb {
+namespace {
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ void store_dz(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_dz(uint16_t* p, float v) {
+  uint32_t u = __float_as_uint(v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  *p = (uint16_t)(u >> 16);
+}
+
+// One workgroup of WAVES wavefronts per row when classes is large, one wavefront per row otherwise.
+template <typename DZ, int WAVES_PER_ROW>
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ logits, int ldz,
+                                                           const int32_t* __restrict__ labels, int rows, int classes,
+                                                           DZ* __restrict__ dz, int lddz, float* __restrict__ row_loss) {
+  constexpr int ROWS_PER_BLOCK = 4 / WAVES_PER_ROW;
+  constexpr int STRIDE = 64 * WAVES_PER_ROW;
+  __shared__ float red[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * ROWS_PER_BLOCK + (WAVES_PER_ROW == 1 ? wave : 0);
+  const bool live = row < rows;                      // uniform per wavefront (per workgroup when WAVES_PER_ROW == 4)
+  const int first = WAVES_PER_ROW == 1 ? lane : (int)threadIdx.x;
+  const float* z = logits + (size_t)(live ? row : 0) * ldz;
+
+  float m = -INFINITY;
+  if (live) for (int c = first; c < classes; c += STRIDE) m = fmaxf(m, z[c]);
+  m = wave_max(m);
+  if (WAVES_PER_ROW > 1) {
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+  }
+  float s = 0.f;
+  if (live) for (int c = first; c < classes; c += STRIDE) s += expf(z[c] - m);
+  s = wave_sum(s);
+  if (WAVES_PER_ROW > 1) {
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    s = (red[0] + red[1]) + (red[2] + red[3]);
+  }
+  if (!live) return;
+  const float lse = m + logf(s);
+  const int y = labels[row];
+  const float inv_rows = 1.f / (float)rows;
+  DZ* out = dz + (size_t)row * lddz;
+  for (int c = first; c < classes; c += STRIDE) {
+    const float p = expf(z[c] - lse);
+    store_dz(out + c, (p - (c == y ? 1.f : 0.f)) * inv_rows);
+  }
+  // a label outside [0, classes) contributes no target term instead of reading out of bounds
+  if (first == 0) row_loss[row] = lse - ((unsigned)y < (unsigned)classes ? z[y] : 0.f);
+}
+
+// Adds the per-row losses in a fixed order (same result on every run) and stores the mean.
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ row_loss, int rows, float* __restrict__ out) {
+  __shared__ float red[4];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < rows; i += 256) s += row_loss[i];
+  s = wave_sum(s);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) out[0] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)rows;
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+}  // namespace
+
+hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labels, int rows, int classes,
+                               void* dz, int lddz, DType dz_dtype, float* row_loss, float* loss_out,
+                               hipStream_t stream) {
+  if (!logits || !labels || !dz || !row_loss || !loss_out || rows <= 0 || classes <= 0 || ldz < classes || lddz < classes)
+    return hipErrorInvalidValue;
+  const bool wide = classes > 2048;
+  const int grid = wide ? rows : (rows + 3) / 4;
+  if (dz_dtype == DType::F32) {
+    if (wide) hipLaunchKernelGGL((softmax_xent_kernel<float, 4>), dim3(grid), dim3(256), 0, stream, logits, ldz, labels, rows, classes, (float*)dz, lddz, row_loss);
+    else hipLaunchKernelGGL((softmax_xent_kernel<float, 1>), dim3(grid), dim3(256), 0, stream, logits, ldz, labels, rows, classes, (float*)dz, lddz, row_loss);
+  } else {
+    if (wide) hipLaunchKernelGGL((softmax_xent_kernel<uint16_t, 4>), dim3(grid), dim3(256), 0, stream, logits, ldz, labels, rows, classes, (uint16_t*)dz, lddz, row_loss);
+    else hipLaunchKernelGGL((softmax_xent_kernel<uint16_t, 1>), dim3(grid), dim3(256), 0, stream, logits, ldz, labels, rows, classes, (uint16_t*)dz, lddz, row_loss);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, stream, row_loss, rows, loss_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream) {
+  if (!ptr || bytes % 4) return hipErrorInvalidValue;
+  if (bytes == 0) return hipSuccess;
+  const size_t words = bytes / 4;
+  const int grid = (int)((words + 255) / 256 < 2048 ? (words + 255) / 256 : 2048);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, stream, (uint32_t*)ptr, words);
+  return hipGetLastError();
+}
+
+}  // namespace spb

@@ -1,0 +1,77 @@
+// Host-side model object behind the C ABI: unit list, parameter list, buffer plan, step drivers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <functional>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "../../include/spb.h"
+#include "kernels.h"
+
+namespace spb {
+
+void set_error(const char* fmt, ...);
+
+struct ParamInfo {
+  std::string name;
+  int unit = 0;
+  DType dtype = DType::BF16;
+  std::vector<int64_t> shape;
+  int64_t numel() const {
+    int64_t n = 1;
+    for (auto d : shape) n *= d;
+    return n;
+  }
+};
+
+// Optional HIP-event bracket around every launch, summed per kernel class.
+class KernelTimer {
+ public:
+  ~KernelTimer();
+  void enable(bool on);
+  bool enabled() const { return enabled_; }
+  hipError_t run(const char* name, double flops, double bytes, hipStream_t stream, const std::function<hipError_t()>& launch);
+  int read(spb_kernel_time* out, int cap, int* n_out);
+
+ private:
+  struct Rec { std::string name; hipEvent_t start, stop; double flops, bytes; };
+  void get_events(hipEvent_t* a, hipEvent_t* b);
+  bool enabled_ = false;
+  std::vector<Rec> recs_;
+  std::vector<hipEvent_t> pool_;
+};
+
+class Model {
+ public:
+  virtual ~Model() = default;
+  virtual size_t workspace_size(int k) const = 0;
+  virtual int forward(const void* x, const int32_t* labels, const int32_t* loss_rows, int k, void* ws, float* loss_out, hipStream_t s) = 0;
+  virtual int backward(int k, hipStream_t s) = 0;
+
+  int num_units = 0;
+  DType dtype = DType::BF16;
+  std::vector<ParamInfo> params;
+  std::vector<void*> param_ptrs, grad_ptrs;
+  bool params_bound = false, grads_bound = false;
+  int stashed_k = -1;  // depth the last forward pass stashed for; -1 = no forward yet
+  void* ws = nullptr;
+  KernelTimer timer;
+
+ protected:
+  int gemm(const GemmProblem& p, hipStream_t s);
+  int check(hipError_t e, const char* what);
+};
+
+std::unique_ptr<Model> make_mlp(const spb_model_desc& d);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace spb
+
+struct spb_model {
+  std::unique_ptr<spb::Model> impl;
+};
