@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Throughput of the SPB worker step on one MI355X, swept over the backprop depth k.
+
+A step is one full forward pass plus the backward pass truncated to the top k units (Sec. 2 of the
+paper) on one synthetic batch that is already resident in HBM.  The timed region replays, for every
+depth of the workload's sweep in turn, a HIP graph that holds exactly the kernels the two C-ABI calls
+enqueue; `--steps` is the total number of timed steps, shared evenly between the depths.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLOP/s, GB/s (MI355X, published)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, params, batch, depths, budget_s):
+    """The oracle as it stands, exact float64 mode, on this host's cores, on a bounded sample."""
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    oracle.spb_step(cfg, params, batch, depths[-1])            # touch everything once, untimed
+    t0 = time.perf_counter()
+    sweeps = 0
+    while True:
+        for k in depths:
+            oracle.spb_step(cfg, params, batch, k)
+        sweeps += 1
+        elapsed = time.perf_counter() - t0
+        if elapsed >= budget_s or elapsed * (sweeps + 1) / sweeps > 2.5 * budget_s:
+            break
+    samples = sweeps * len(depths) * cfg["batch"]
+    return {"value": samples / elapsed, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{cfg['name']} full batch of {cfg['batch']}, {sweeps} sweep(s) over depths {depths}, "
+                      f"float64 exact mode, {elapsed:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs one worker's step on ONE GPU; no multi-GPU path exists. "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2111_10672_amd as spb
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the SPB path has no host fallback.", file=sys.stderr)
+        sys.exit(2)
+
+    cfg = wl.get_config(args.config)
+    depths = wl.depth_sweep(cfg)
+    params, batch = wl.make_params(cfg, 0), wl.make_batch(cfg, 0)
+    model = spb.SpbModel(cfg, params, "cuda:0")
+    dev = {n: t.cuda() for n, t in batch.items()}
+    model.reserve(max(depths))
+    per_depth = max(1, -(-args.steps // len(depths)))
+    steps = per_depth * len(depths)
+    warm_per_depth = max(1, -(-args.warmup // len(depths)))
+
+    # One HIP graph per depth: the kernels of spb_forward(k) + spb_backward_truncated(k), nothing else.
+    stream = torch.cuda.Stream()
+    graphs = {}
+    with torch.cuda.stream(stream):
+        for k in depths:
+            model.step(dev, k)
+        stream.synchronize()
+        for k in depths:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                model.step(dev, k)
+            graphs[k] = g
+        for k in depths:
+            for _ in range(warm_per_depth):
+                graphs[k].replay()
+        stream.synchronize()
+        # ---- timed region: exactly `steps` steps -------------------------------------------------
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(len(depths) + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        marks[0].record(stream)
+        for i, k in enumerate(depths):
+            g = graphs[k]
+            for _ in range(per_depth):
+                g.replay()
+            marks[i + 1].record(stream)
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3
+        depth_ms = [marks[i].elapsed_time(marks[i + 1]) / per_depth for i in range(len(depths))]
+        total_ms = marks[0].elapsed_time(marks[-1])
+
+        # ---- the same steps launched eagerly, every kernel bracketed by HIP events on this stream ----
+        timing_steps = max(20, min(200, per_depth))
+        spb.spb_set_kernel_timing(model.handle, True)
+        for _ in range(timing_steps):
+            for k in depths:
+                model.step(dev, k)
+        stream.synchronize()
+        kernels = spb.spb_read_kernel_timing(model.handle)
+        spb.spb_set_kernel_timing(model.handle, False)
+
+    ms_per_step = total_ms / steps
+    value = cfg["batch"] / (ms_per_step * 1e-3)
+    is_f32 = cfg["dtype"] == "f32"
+    mfma_peak = PEAK["mfma_f32" if is_f32 else "mfma_bf16"]
+    table = []
+    for r in kernels:
+        avg_us = r["total_ms"] / r["launches"] * 1e3
+        table.append({"name": r["name"], "launches_per_sweep": r["launches"] / timing_steps, "avg_us": round(avg_us, 3),
+                      "tflops": round(r["flops"] / r["total_ms"] / 1e9, 3) if r["flops"] else None,
+                      "gbps": round(r["bytes"] / r["total_ms"] / 1e6, 2)})
+    gemms = [r for r in kernels if r["flops"] > 0]
+    dom = max(gemms or kernels, key=lambda r: r["total_ms"])
+    if dom["flops"] > 0:
+        achieved = dom["flops"] / dom["total_ms"] / 1e9          # TFLOP/s
+        roofline = {"kernel": dom["name"], "bound": "mfma", "achieved": round(achieved, 3), "peak": mfma_peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / mfma_peak, 5), "traffic": None,
+                    "avg_launch_us": round(dom["total_ms"] / dom["launches"] * 1e3, 3),
+                    "flops_per_launch": dom["flops"] / dom["launches"],
+                    "hbm_gbps_at_min_bytes": round(dom["bytes"] / dom["total_ms"] / 1e6, 2)}
+    else:
+        achieved = dom["bytes"] / dom["total_ms"] / 1e6
+        roofline = {"kernel": dom["name"], "bound": "hbm", "achieved": round(achieved, 2), "peak": PEAK["hbm"],
+                    "unit": "GB/s", "frac": round(achieved / PEAK["hbm"], 5), "traffic": None}
+
+    out = {
+        "metric": "SPB train-step samples/sec vs backprop depth k; % MFMA peak (bwd GEMMs)",
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": warm_per_depth * len(depths),
+        "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if is_f32 else "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: {cfg['family']} {cfg['dims'] if 'dims' in cfg else ''} batch {cfg['batch']}, "
+                               f"depth sweep k={depths}, steps shared evenly between depths",
+                   "launch": "hip_graph_replay", "steps_per_depth": per_depth},
+        "samples_per_s_by_depth": {str(k): round(cfg["batch"] / (ms * 1e-3), 1) for k, ms in zip(depths, depth_ms)},
+        "ms_by_depth": {str(k): round(ms, 6) for k, ms in zip(depths, depth_ms)},
+        "workspace_bytes_by_depth": {str(k): spb.spb_workspace_size(model.handle, k) for k in depths},
+        "wall_ms_timed_region": round(wall_ms, 3),
+        "roofline": roofline,
+        "kernels": table,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, params, batch, depths, args.cpu_seconds)
+    model.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -16,40 +16,11 @@
 // consecutive rows, same chunk) nor the transposed writes (rows 8 apart) pile onto one bank group.
 // Global loads for tile t+1 are in flight while tile t is multiplied (register prefetch, two LDS
 // buffers, one barrier per tile).
-#include "kernels.h"
+#include "gemm_common.h"
 
 namespace spb {
+using namespace gemm_detail;
 namespace {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-struct bf16_t { uint16_t bits; };
-
-constexpr int kThreads = 256;
-constexpr int kRowBytes = 128;  // bytes of k per LDS row and per tile step
-constexpr int kChunks = 8;      // 16-byte chunks per LDS row
-
-template <typename T> struct Elem;
-template <> struct Elem<float> { static constexpr int kPerChunk = 4; static constexpr int kTileK = 32; };
-template <> struct Elem<bf16_t> { static constexpr int kPerChunk = 8; static constexpr int kTileK = 64; };
-
-__device__ __forceinline__ int lds_offset(int row, int chunk) {
-  return row * kRowBytes + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
-}
-
-__device__ __forceinline__ float to_float(float v) { return v; }
-__device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float(((uint32_t)v.bits) << 16); }
-
-__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
-__device__ __forceinline__ void store_elem(bf16_t* p, float v) {
-  // round to nearest, ties to even, on the upper 16 bits of the float32 pattern
-  uint32_t u = __float_as_uint(v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  p->bits = (uint16_t)(u >> 16);
-}
 
 // ---- operand loaders: global -> registers -> LDS [row][k] ------------------------------------
 
@@ -185,14 +156,6 @@ __device__ __forceinline__ f32x16 mma(float, u32x4 a, u32x4 b, f32x16 c) {
   return c;
 }
 
-struct GemmParams {
-  const void* A; const void* B; void* C;
-  const void* bias; const void* mask; float* a_row_sum;
-  int M, N, K, lda, ldb, ldc, ldmask;
-  int epilogue, relu;
-  int tiles_m, tiles_n;
-};
-
 template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams p) {
   static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
@@ -205,11 +168,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams p) {
   auto a_buf = [&](int i) { return lds + i * (BM * kRowBytes); };
   auto b_buf = [&](int i) { return lds + 2 * BM * kRowBytes + i * (BN * kRowBytes); };
 
-  // Consecutive workgroup ids land on different XCDs (round-robin over 8); give each XCD a
-  // contiguous run of tiles so that neighbours in a run share operand rows in that XCD's L2.
-  const int n_tiles = p.tiles_m * p.tiles_n;
-  int tile = blockIdx.x;
-  if (n_tiles % 8 == 0) tile = (blockIdx.x & 7) * (n_tiles >> 3) + (blockIdx.x >> 3);
+  const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
   const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
@@ -284,44 +243,12 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmParams p) {
 
   if (want_row_sum && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = row_sum;
 
-  // Accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block.
-  const T* bias = static_cast<const T*>(p.bias);
-  const T* mask = static_cast<const T*>(p.mask);
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * WN + j * 32 + (lane & 31);
-      if (n >= p.N) continue;
-      const float bv = bias ? to_float(bias[n]) : 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m >= p.M) continue;
-        float v = acc[i][j][r];
-        if (p.epilogue == (int)Epilogue::StoreF32) {
-          static_cast<float*>(p.C)[(size_t)m * p.ldc + n] = v + bv;
-        } else if (p.epilogue == (int)Epilogue::BiasAct) {
-          v += bv;
-          if (p.relu) v = fmaxf(v, 0.f);
-          store_elem(static_cast<T*>(p.C) + (size_t)m * p.ldc + n, v);
-        } else {
-          if (!(to_float(mask[(size_t)m * p.ldmask + n]) > 0.f)) v = 0.f;
-          store_elem(static_cast<T*>(p.C) + (size_t)m * p.ldc + n, v);
-        }
-      }
-    }
-  }
+  store_tile<T, TM, TN>(p, acc, m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <typename T, int BM, int BN, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
 hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
-  GemmParams p;
-  p.A = q.A; p.B = q.B; p.C = q.C; p.bias = q.bias; p.mask = q.mask; p.a_row_sum = q.a_row_sum;
-  p.M = q.M; p.N = q.N; p.K = q.K; p.lda = q.lda; p.ldb = q.ldb; p.ldc = q.ldc; p.ldmask = q.ldmask;
-  p.epilogue = (int)q.epilogue; p.relu = q.relu;
-  p.tiles_m = (q.M + BM - 1) / BM;
-  p.tiles_n = (q.N + BN - 1) / BN;
+  GemmParams p = make_params(q, BM, BN);
   const size_t lds_bytes = (size_t)2 * (BM + BN) * kRowBytes;
   auto kernel = gemm_kernel<T, BM, BN, WAVES_M, WAVES_N, LA, LB>;
   if (lds_bytes > 64 * 1024) {
@@ -375,6 +302,7 @@ hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream) {
   if (p.ldc < p.N) return hipErrorInvalidValue;
   if (p.epilogue == Epilogue::MaskStore && (!p.mask || p.ldmask < p.N)) return hipErrorInvalidValue;
   if (p.dtype == DType::F32) return launch_typed<float>(p, stream);
+  if (gemm_dma_accepts(p)) return launch_gemm_dma(p, stream);
   return launch_typed<bf16_t>(p, stream);
 }
 

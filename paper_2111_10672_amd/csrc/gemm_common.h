@@ -1,0 +1,96 @@
+// Pieces shared by the GEMM kernels: vector types, bfloat16 storage helpers, kernel parameters, epilogue.
+#pragma once
+#include "kernels.h"
+
+namespace spb {
+namespace gemm_detail {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct bf16_t { uint16_t bits; };
+
+constexpr int kThreads = 256;
+constexpr int kRowBytes = 128;  // bytes of k per LDS row and per tile step
+constexpr int kChunks = 8;      // 16-byte chunks per LDS row
+
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int kPerChunk = 4; static constexpr int kTileK = 32; };
+template <> struct Elem<bf16_t> { static constexpr int kPerChunk = 8; static constexpr int kTileK = 64; };
+
+__device__ __forceinline__ int lds_offset(int row, int chunk) {
+  return row * kRowBytes + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
+}
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float(((uint32_t)v.bits) << 16); }
+
+__device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_elem(bf16_t* p, float v) {
+  // round to nearest, ties to even, on the upper 16 bits of the float32 pattern
+  uint32_t u = __float_as_uint(v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  p->bits = (uint16_t)(u >> 16);
+}
+
+struct GemmParams {
+  const void* A; const void* B; void* C;
+  const void* bias; const void* mask; float* a_row_sum;
+  int M, N, K, lda, ldb, ldc, ldmask;
+  int epilogue, relu;
+  int tiles_m, tiles_n;
+};
+
+
+// Accumulator register r of lane l of a 32x32 MFMA block holds C[8*(r/4) + 4*(l/32) + r%4][l%32].
+template <typename T, int TM, int TN>
+__device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM][TN], int row_base, int col_base, int lane) {
+  const T* bias = static_cast<const T*>(p.bias);
+  const T* mask = static_cast<const T*>(p.mask);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = col_base + j * 32 + (lane & 31);
+      if (n >= p.N) continue;
+      const float bv = bias ? to_float(bias[n]) : 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = row_base + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m >= p.M) continue;
+        float v = acc[i][j][r];
+        if (p.epilogue == (int)Epilogue::StoreF32) {
+          static_cast<float*>(p.C)[(size_t)m * p.ldc + n] = v + bv;
+        } else if (p.epilogue == (int)Epilogue::BiasAct) {
+          v += bv;
+          if (p.relu) v = fmaxf(v, 0.f);
+          store_elem(static_cast<T*>(p.C) + (size_t)m * p.ldc + n, v);
+        } else {
+          if (!(to_float(mask[(size_t)m * p.ldmask + n]) > 0.f)) v = 0.f;
+          store_elem(static_cast<T*>(p.C) + (size_t)m * p.ldc + n, v);
+        }
+      }
+    }
+  }
+}
+
+inline GemmParams make_params(const GemmProblem& q, int bm, int bn) {
+  GemmParams p;
+  p.A = q.A; p.B = q.B; p.C = q.C; p.bias = q.bias; p.mask = q.mask; p.a_row_sum = q.a_row_sum;
+  p.M = q.M; p.N = q.N; p.K = q.K; p.lda = q.lda; p.ldb = q.ldb; p.ldc = q.ldc; p.ldmask = q.ldmask;
+  p.epilogue = (int)q.epilogue; p.relu = q.relu;
+  p.tiles_m = (q.M + bm - 1) / bm;
+  p.tiles_n = (q.N + bn - 1) / bn;
+  return p;
+}
+
+// Consecutive workgroup ids land on different XCDs (round-robin over 8); give each XCD a contiguous
+// run of tiles so that neighbours in a run share operand rows in that XCD's L2.
+__device__ __forceinline__ int xcd_tile(int block, int n_tiles) {
+  return n_tiles % 8 == 0 ? (block & 7) * (n_tiles >> 3) + (block >> 3) : block;
+}
+
+}  // namespace gemm_detail
+}  // namespace spb

@@ -1,0 +1,377 @@
+// bfloat16 products on the gfx950 matrix cores with direct-to-LDS operand loads.
+//
+//   C[m, n] = sum_k A(m, k) * B(n, k),   float32 accumulation
+//
+// Same three products as gemm.hip (forward, input gradient, weight gradient of a dense layer), built
+// around two CDNA4 facilities:
+//   * global_load_lds_dwordx4: every lane fetches 16 bytes from its own global address and the wave's
+//     64 chunks land in one contiguous KiB of LDS, without passing through registers.  Several tiles
+//     can therefore be in flight at once (STAGES-deep ring); which chunk a lane fetches is chosen so
+//     that the KiB it fills is already in the bank-friendly order the matrix-core reads want.
+//   * ds_read_b64_tr_b16: a transposing LDS read.  An operand whose *row* index is contiguous in memory
+//     (the layout of both weight-gradient operands and of W in the input-gradient product) is copied to
+//     LDS as it lies and transposed on the way to the registers.  Within 16 lanes, lane j receives
+//     element (j % 4) of the 8-byte words read by lanes j/4, j/4 + 4, j/4 + 8, j/4 + 12; pointing lane j'
+//     at 4 consecutive rows starting at row 4 * (j' % 4) of k-row j'/4 gives lane j four consecutive k
+//     of row j, which is the MFMA operand layout.
+// Tile loop: wait for tile t (s_waitcnt vmcnt leaves the younger tiles' loads in flight), one barrier,
+// issue tile t + STAGES - 1 into the buffer tile t - 1 used, multiply tile t.
+#include "gemm_common.h"
+
+namespace spb {
+using namespace gemm_detail;
+namespace {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* global_ptr_t;
+
+__device__ const uint32_t kZeroChunk[4] = {0u, 0u, 0u, 0u};
+
+constexpr int kTileK = 64;  // bfloat16 elements of k per tile: 128 bytes per row
+
+// s_waitcnt immediate for gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no wait), lgkmcnt 11:8.
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 15) << 8); }
+
+template <int VM>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM, 0));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Rotation (in 16-byte chunks) of k-row k of a KRow tile, so that the four k-rows one transposing read
+// touches fall into different 64-byte bank groups.
+template <int ROWS>
+__device__ __forceinline__ int krow_rot(int k) {
+  if constexpr (ROWS >= 128) return (k & 3) << 2;
+  else if constexpr (ROWS == 64) return ((k >> 1) & 1) << 2;
+  else return 0;
+}
+
+// Where one lane's 16-byte chunks of an operand tile come from.  Everything that does not change from
+// tile to tile is worked out once: per tile a lane adds the tile's byte offset and checks the k bound.
+// Every wave issues exactly kInstr direct-to-LDS instructions per tile, whatever its lanes' predicates:
+// a lane outside the matrix fetches a chunk of zeros instead, so the vmcnt arithmetic of the tile loop
+// holds and rows or k beyond the matrix multiply as zero.
+template <int ROWS, Layout L, int NW>
+struct TileSource {
+  static constexpr int kInstr = ROWS / (8 * NW);
+  static_assert(ROWS % (8 * NW) == 0 && kInstr >= 1, "tile rows must fill whole wave instructions");
+  const char* ptr[kInstr];  // this lane's chunk in tile 0 (not dereferenced unless in range)
+  int k_in_tile[kInstr];    // k of the chunk's first element relative to the tile start
+  bool in_rows[kInstr];
+  size_t tile_step;         // bytes from one tile to the next
+
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int wave, int lane) {
+    tile_step = L == Layout::RowK ? (size_t)kTileK * 2 : (size_t)kTileK * ld * 2;
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const int slot = (i * NW + wave) * 64 + lane;
+      int gr, k;
+      if constexpr (L == Layout::RowK) {
+        const int row = slot >> 3, pc = slot & 7;
+        gr = row0 + row;
+        k = ((pc ^ row ^ (row >> 3)) & 7) << 3;
+        ptr[i] = reinterpret_cast<const char*>(base + (size_t)gr * ld + k);
+      } else {
+        constexpr int kRowChunks = ROWS / 8;
+        k = slot / kRowChunks;
+        const int pc = slot % kRowChunks;
+        gr = row0 + (((pc - krow_rot<ROWS>(k)) & (kRowChunks - 1)) << 3);
+        ptr[i] = reinterpret_cast<const char*>(base + (size_t)k * ld + gr);
+      }
+      k_in_tile[i] = k;
+      in_rows[i] = gr < nrows;
+    }
+  }
+  __device__ __forceinline__ void issue(int t, int K, char* tile, int wave) const {
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const char* src = reinterpret_cast<const char*>(kZeroChunk);
+      if (in_rows[i] && t * kTileK + k_in_tile[i] < K) src = ptr[i] + (size_t)t * tile_step;
+      __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, 0, 0);
+    }
+  }
+};
+
+// Fetch the MFMA operand of one 32-row fragment for k-group kg (16 values of k): 8 bfloat16 per lane.
+// A KRow fragment is read in assembly and is valid only after fragments_ready().
+template <int ROWS, Layout L>
+__device__ __forceinline__ u32x4 read_fragment(const char* tile, int frag_row0, int kg, int lane) {
+  if constexpr (L == Layout::RowK) {
+    return *reinterpret_cast<const u32x4*>(tile + lds_offset(frag_row0 + (lane & 31), 2 * kg + (lane >> 5)));
+  } else {
+    constexpr int kRowChunks = ROWS / 8;
+    const int j = lane & 15, g = lane >> 4;
+    const int row = frag_row0 + 16 * (g & 1) + 4 * (j & 3);  // first of the 4 rows this lane's word covers
+    u32x4 out;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k = 16 * kg + 8 * (g >> 1) + 4 * h + (j >> 2);
+      const int pc = ((row >> 3) + krow_rot<ROWS>(k)) & (kRowChunks - 1);
+      const char* addr = tile + k * (ROWS * 2) + pc * 16 + (row & 7) * 2;
+      // Written as assembly: through the builtin the compiler cannot tell this read from the in-flight
+      // direct-to-LDS tiles and drains them all (vmcnt 0) first.
+      const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)addr;
+      uint2 w;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(w) : "v"(lds_addr));
+      out[2 * h] = w.x;
+      out[2 * h + 1] = w.y;
+    }
+    return out;
+  }
+}
+
+// Wait for the LDS reads issued in assembly and pin every later use of the fragments behind the wait.
+template <int NA, int NB>
+__device__ __forceinline__ void fragments_ready(u32x4 (&a)[NA], u32x4 (&b)[NB]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < NA; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+  for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
+}
+
+// Epilogue.  Each wave parks its WM x WN accumulator tile in its own LDS region (the tile ring is dead by
+// then) and reads it back row by row, so that bias, mask and result move in 16-byte pieces along n.
+template <int WM, int WN>
+__device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage,
+                                                int row_base, int col_base, int lane) {
+  constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of rows 4 apart
+#pragma unroll
+  for (int i = 0; i < WM / 32; ++i)
+#pragma unroll
+    for (int j = 0; j < WN / 32; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage[(i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[i][j][r];
+  // same wave wrote and reads: LDS operations of one wave complete in order
+  const bf16_t* bias = static_cast<const bf16_t*>(p.bias);
+  if (p.epilogue == (int)Epilogue::StoreF32) {
+    constexpr int kUnits = WM * WN / 4;
+#pragma unroll
+    for (int it = 0; it < kUnits / 64; ++it) {
+      const int u = it * 64 + lane;
+      const int row = u / (WN / 4), c = (u % (WN / 4)) * 4;
+      const int m = row_base + row, n = col_base + c;
+      if (m >= p.M || n >= p.N) continue;
+      f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
+      float* dst = static_cast<float*>(p.C) + (size_t)m * p.ldc + n;
+      if (n + 4 <= p.N) {
+        if (bias) {
+          const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+          v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+          v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+        }
+        *reinterpret_cast<f32x4*>(dst) = v;
+      } else {
+        for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e] + (bias ? to_float(bias[n + e]) : 0.f);
+      }
+    }
+  } else {
+    constexpr int kUnits = WM * WN / 8;
+    const bool masked = p.epilogue == (int)Epilogue::MaskStore;
+    const bf16_t* mask = static_cast<const bf16_t*>(p.mask);
+#pragma unroll
+    for (int it = 0; it < kUnits / 64; ++it) {
+      const int u = it * 64 + lane;
+      const int row = u / (WN / 8), c = (u % (WN / 8)) * 8;
+      const int m = row_base + row, n = col_base + c;
+      if (m >= p.M || n >= p.N) continue;
+      float v[8];
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
+      const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
+      bf16_t* dst = static_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n;
+      if (n + 8 <= p.N) {
+        if (masked) {
+          const u32x4 mk = *reinterpret_cast<const u32x4*>(mask + (size_t)m * p.ldmask + n);
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            if (!(__uint_as_float(mk[d] << 16) > 0.f)) v[2 * d] = 0.f;
+            if (!(__uint_as_float(mk[d] & 0xFFFF0000u) > 0.f)) v[2 * d + 1] = 0.f;
+          }
+        } else {
+          if (bias) {
+            const u32x4 bb = *reinterpret_cast<const u32x4*>(bias + n);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) { v[2 * d] += __uint_as_float(bb[d] << 16); v[2 * d + 1] += __uint_as_float(bb[d] & 0xFFFF0000u); }
+          }
+          if (p.relu) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+          }
+        }
+        u32x4 o;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) o[d] = pack_bf16(v[2 * d], v[2 * d + 1]);
+        *reinterpret_cast<u32x4*>(dst) = o;
+      } else {
+        for (int e = 0; e < 8 && n + e < p.N; ++e) {
+          float x = v[e];
+          if (masked) { if (!(to_float(mask[(size_t)m * p.ldmask + n + e]) > 0.f)) x = 0.f; }
+          else { if (bias) x += to_float(bias[n + e]); if (p.relu) x = fmaxf(x, 0.f); }
+          store_elem(dst + e, x);
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(GemmParams p) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
+  static_assert(STAGES >= 2 && STAGES <= 8, "ring depth");
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(TM >= 1 && TN >= 1 && WM % 32 == 0 && WN % 32 == 0, "wave tile is a multiple of 32x32");
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  constexpr int kLoadsPerTile = (BM + BN) / (8 * NW);  // direct-to-LDS instructions per wave per tile
+  constexpr int kBatch = (TM + TN) <= 2 ? 4 : ((TM + TN) <= 4 ? 2 : 1);  // k-groups whose fragments are fetched together
+  static_assert((size_t)NW * WM * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
+  const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+
+  TileSource<BM, LA, NW> src_a;
+  TileSource<BN, LB, NW> src_b;
+  src_a.init(static_cast<const bf16_t*>(p.A), p.lda, m0, p.M, wave, lane);
+  src_b.init(static_cast<const bf16_t*>(p.B), p.ldb, n0, p.N, wave, lane);
+  const int n_steps = (p.K + kTileK - 1) / kTileK;
+  auto issue = [&](int t) {
+    char* stage = lds + (t % STAGES) * kStageBytes;
+    src_a.issue(t, p.K, stage, wave);
+    src_b.issue(t, p.K, stage + BM * kRowBytes, wave);
+  };
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < n_steps) issue(s);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const bool want_row_sum = LA == Layout::KRow && p.a_row_sum != nullptr && tile_n == 0;
+  float row_sum = 0.f;
+
+  for (int t = 0; t < n_steps; ++t) {
+    // Tiles t+1 .. t+STAGES-2 may stay in flight if they were all issued; near the end wait for everything.
+    if (t + STAGES - 2 < n_steps) wait_loads_and_barrier<(STAGES - 2) * kLoadsPerTile>();
+    else wait_loads_and_barrier<0>();
+    if (t + STAGES - 1 < n_steps) issue(t + STAGES - 1);
+    const char* as = lds + (t % STAGES) * kStageBytes;
+    const char* bs = as + BM * kRowBytes;
+#pragma unroll
+    for (int kb = 0; kb < 4; kb += kBatch) {
+      u32x4 a[kBatch * TM], b[kBatch * TN];
+#pragma unroll
+      for (int g = 0; g < kBatch; ++g) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[g * TM + i] = read_fragment<BM, LA>(as, wm * WM + i * 32, kb + g, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[g * TN + j] = read_fragment<BN, LB>(bs, wn * WN + j * 32, kb + g, lane);
+      }
+      if constexpr (LA == Layout::KRow || LB == Layout::KRow) fragments_ready(a, b);
+#pragma unroll
+      for (int g = 0; g < kBatch; ++g)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[g * TM + i]),
+                                                                __builtin_bit_cast(bf16x8, b[g * TN + j]), acc[i][j], 0, 0, 0);
+      if constexpr (LA == Layout::RowK && LB == Layout::RowK) {
+        // Keep the batch's LDS reads ahead of its MFMAs (the scheduler otherwise sinks each read to its use
+        // and the wave eats one LDS latency per MFMA).
+        __builtin_amdgcn_sched_group_barrier(0x100, kBatch * (TM + TN), 0);  // DS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, kBatch * TM * TN, 0);    // MFMA
+      }
+    }
+    if constexpr (LA == Layout::KRow) {
+      if (want_row_sum && threadIdx.x < BM) {  // bias gradient: sum over k of A(row, k), tile rows lie along the LDS row
+        const int row = threadIdx.x;
+#pragma unroll 8
+        for (int k = 0; k < kTileK; ++k) {
+          const int pc = ((row >> 3) + krow_rot<BM>(k)) & (BM / 8 - 1);
+          const uint16_t bits = *reinterpret_cast<const uint16_t*>(as + k * (BM * 2) + pc * 16 + (row & 7) * 2);
+          row_sum += __uint_as_float(((uint32_t)bits) << 16);
+        }
+      }
+    }
+  }
+  if (want_row_sum && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = row_sum;
+  wait_loads_and_barrier<0>();  // every wave is done with the tile ring
+  float* stage = reinterpret_cast<float*>(lds) + wave * (WM * (WN + 4));
+  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane);
+}
+
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
+hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
+  GemmParams p = make_params(q, BM, BN);
+  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kRowBytes;
+  static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, LA, LB>;
+  if (lds_bytes > 64 * 1024) {
+    static bool raised = false;  // per instantiation
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
+template <Layout LA, Layout LB>
+hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
+  const long big_tiles = (long)((q.M + 127) / 128) * ((q.N + 127) / 128);
+  if (big_tiles >= 192) return launch_tile<128, 128, 3, 2, 2, LA, LB>(q, stream);
+  return launch_tile<64, 64, 4, 2, 2, LA, LB>(q, stream);
+}
+
+}  // namespace
+
+bool gemm_dma_accepts(const GemmProblem& p) {
+  if (p.dtype != DType::BF16) return false;
+  // A partly filled 16-byte chunk along the contiguous index is fetched whole: allowed only where the
+  // owner of the buffer keeps the rest of the chunk zero.
+  auto ok = [&](Layout l, int rows, bool pad_zero) { return ((l == Layout::RowK ? p.K : rows) % 8 == 0) || pad_zero; };
+  if (!ok(p.a_layout, p.M, p.a_pad_zero) || !ok(p.b_layout, p.N, p.b_pad_zero)) return false;
+  // The epilogue moves 16 bytes at a time along n.
+  auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+  const int per_out = p.epilogue == Epilogue::StoreF32 ? 4 : 8;
+  if (p.ldc % per_out || !a16(p.C)) return false;
+  if (p.bias && !a16(p.bias)) return false;
+  if (p.epilogue == Epilogue::MaskStore && (p.ldmask % 8 || !a16(p.mask))) return false;
+  return true;
+}
+
+hipError_t launch_gemm_dma(const GemmProblem& p, hipStream_t stream) {
+  if (p.a_layout == Layout::RowK && p.b_layout == Layout::RowK) return launch_layouts<Layout::RowK, Layout::RowK>(p, stream);
+  if (p.a_layout == Layout::RowK && p.b_layout == Layout::KRow) return launch_layouts<Layout::RowK, Layout::KRow>(p, stream);
+  if (p.a_layout == Layout::KRow && p.b_layout == Layout::KRow) return launch_layouts<Layout::KRow, Layout::KRow>(p, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace spb

@@ -33,6 +33,9 @@ struct GemmProblem {
   const void* bias = nullptr;     // [N], dtype
   int relu = 0;
   const void* mask = nullptr; int ldmask = 0;   // [M, N], dtype
+  // The buffer's owner keeps zeros between the end of each row's data and the next multiple of 8 elements
+  // along the contiguous index (lets a kernel fetch whole 16-byte chunks).
+  bool a_pad_zero = false, b_pad_zero = false;
   float* a_row_sum = nullptr;     // optional [M]: sum_k A(m, k), written once by the tiles of column block 0
   const char* name = "gemm";
 };
@@ -40,11 +43,14 @@ struct GemmProblem {
 // Checks shapes and alignment on the host, then enqueues one kernel.  Returns hipSuccess,
 // hipErrorInvalidValue for a problem the kernel cannot take, or the launch error.
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
+bool gemm_dma_accepts(const GemmProblem& p);
+hipError_t launch_gemm_dma(const GemmProblem& p, hipStream_t stream);
 double gemm_flops(const GemmProblem& p);
 double gemm_bytes(const GemmProblem& p);
 
 // Softmax cross-entropy over `rows` rows of float32 logits [rows, ldz], `classes` used columns.
-// Writes dz (dtype, [rows, lddz]) = (softmax - onehot) / rows, row_loss[rows] (float32), then a
+// Writes dz (dtype, [rows, lddz]) = (softmax - onehot) / rows with zeros in columns classes..lddz-1,
+// row_loss[rows] (float32), then a
 // second kernel adds row_loss up in a fixed order into loss_out[0] = mean.
 hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labels, int rows, int classes,
                                void* dz, int lddz, DType dz_dtype, float* row_loss, float* loss_out,

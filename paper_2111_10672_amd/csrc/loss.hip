@@ -66,6 +66,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
     store_dz(out + c, (p - (c == y ? 1.f : 0.f)) * inv_rows);
   }
   // a label outside [0, classes) contributes no target term instead of reading out of bounds
+  for (int c = classes + first; c < lddz; c += STRIDE) store_dz(out + c, 0.f);  // keep the pitch padding zero
   if (first == 0) row_loss[row] = lse - ((unsigned)y < (unsigned)classes ? z[y] : 0.f);
 }
 

@@ -118,6 +118,7 @@ class MlpModel : public Model {
       w.A = dz; w.lda = ld_dz; w.B = a_u; w.ldb = ld_a;
       w.C = grad_ptrs[2 * u]; w.ldc = n_in; w.epilogue = Epilogue::StoreF32;
       w.a_row_sum = static_cast<float*>(grad_ptrs[2 * u + 1]);
+      w.a_pad_zero = w.b_pad_zero = true;  // dz: padding zeroed by its producer; activations have none
       w.name = dtype == DType::F32 ? "gemm_f32_wgrad" : "gemm_bf16_wgrad";
       if (int rc = gemm(w, s)) return rc;
       if (u == L - k) break;  // lowest visited unit: no input gradient (nothing below consumes it)
@@ -127,6 +128,7 @@ class MlpModel : public Model {
       d.A = dz; d.lda = ld_dz; d.B = param_ptrs[2 * u]; d.ldb = n_in;
       d.C = base + p.dz[u & 1]; d.ldc = ld(u);
       d.epilogue = Epilogue::MaskStore; d.mask = a_u; d.ldmask = ld_a;
+      d.a_pad_zero = d.b_pad_zero = true;
       d.name = dtype == DType::F32 ? "gemm_f32_dgrad" : "gemm_bf16_dgrad";
       if (int rc = gemm(d, s)) return rc;
       dz = d.C; ld_dz = d.ldc;
