@@ -46,3 +46,57 @@ def softmax_ce(z, labels):
     dz = np.exp(z - lse)
     dz[np.arange(rows), labels] -= 1.0
     return loss, dz / rows
+
+
+# ---- Transformer encoder operations --------------------------------------------------------------
+
+LN_EPS = 1e-5
+
+
+def layernorm_fwd(x, gamma, beta):
+    """Per row: mu = mean(x), var = mean((x - mu)^2) (biased), xhat = (x - mu) / sqrt(var + eps), y = gamma * xhat + beta."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + LN_EPS)
+    xhat = (x - mu) * rstd
+    return gamma * xhat + beta, (xhat, rstd)
+
+
+def layernorm_bwd(dy, gamma, cache):
+    """g = dy * gamma; dx = (g - mean(g) - xhat * mean(g * xhat)) * rstd; dgamma = sum_rows dy * xhat; dbeta = sum_rows dy."""
+    xhat, rstd = cache
+    g = dy * gamma
+    dx = (g - g.mean(axis=-1, keepdims=True) - xhat * (g * xhat).mean(axis=-1, keepdims=True)) * rstd
+    return dx, (dy * xhat).sum(axis=0), dy.sum(axis=0)
+
+
+def _erf(x):
+    from scipy.special import erf
+    return erf(x)
+
+
+def gelu_fwd(x):
+    """Exact GELU: x * Phi(x) with the normal distribution function Phi(x) = (1 + erf(x / sqrt 2)) / 2."""
+    return 0.5 * x * (1.0 + _erf(x / np.sqrt(2.0)))
+
+
+def gelu_grad(x):
+    """d/dx [x Phi(x)] = Phi(x) + x phi(x), phi the normal density."""
+    return 0.5 * (1.0 + _erf(x / np.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / np.sqrt(2.0 * np.pi)
+
+
+def softmax_rows(s):
+    e = np.exp(s - s.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def split_heads(t, batch, seq, heads):
+    """[batch * seq, heads * d] -> [batch, heads, seq, d]."""
+    d = t.shape[1] // heads
+    return t.reshape(batch, seq, heads, d).transpose(0, 2, 1, 3)
+
+
+def merge_heads(t):
+    """[batch, heads, seq, d] -> [batch * seq, heads * d]."""
+    b, h, s, d = t.shape
+    return t.transpose(0, 2, 1, 3).reshape(b * s, h * d)

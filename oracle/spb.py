@@ -51,6 +51,8 @@ def build_units(cfg):
     if fam == "mlp":
         n = len(cfg["dims"]) - 1
         return [LinearUnit(i, relu=(i < n - 1), loss=(i == n - 1)) for i in range(n)]
+    if fam == "encoder":
+        return [EmbeddingUnit(cfg)] + [EncoderLayerUnit(i, cfg) for i in range(cfg["layers"])] + [MaskedHeadUnit()]
     raise NotImplementedError(fam)
 
 
@@ -73,7 +75,7 @@ def spb_step(cfg, params, batch, k, q=identity):
         raise ValueError(f"depth {k} outside 0..{n_units}")
     p = {name: _as_f64(v) for name, v in params.items()}
     b = {name: _as_f64(v) for name, v in batch.items()}
-    h = b["x"] if "x" in b else None
+    h = b["x"]
     for unit in units:                            # the forward pass is always complete
         h = unit.forward(h, p, q, b)
     loss = h
@@ -84,3 +86,111 @@ def spb_step(cfg, params, batch, k, q=identity):
         g, dout = units[index].backward(dout, p, q, need_input_grad=not lowest)
         grads.update(g)
     return loss, grads
+
+
+class EmbeddingUnit:
+    """x0[b, s, :] = tok[id[b, s], :] + pos[s, :].  Its gradient is a scatter-add of rows; it is the lowest
+    unit, so it never forms an input gradient."""
+
+    param_names = ["embed.tok.weight", "embed.pos.weight"]
+
+    def __init__(self, cfg):
+        self.seq = cfg["seq"]
+
+    def forward(self, _x, p, q, batch):
+        self.ids = batch["x"].reshape(-1)
+        tok, pos = p["embed.tok.weight"], p["embed.pos.weight"]
+        self.shapes = tok.shape, pos.shape
+        n = self.ids.shape[0]
+        return q(tok[self.ids] + pos[np.arange(n) % self.seq])
+
+    def backward(self, dout, p, q, need_input_grad):
+        dtok, dpos = np.zeros(self.shapes[0]), np.zeros(self.shapes[1])
+        for row in range(dout.shape[0]):           # duplicates add up
+            dtok[self.ids[row]] += dout[row]
+            dpos[row % self.seq] += dout[row]
+        return {"embed.tok.weight": dtok, "embed.pos.weight": dpos}, None
+
+
+class EncoderLayerUnit:
+    """Pre-LayerNorm Transformer layer: h = x + Out(Attn(LN1 x)); out = h + W2 gelu(W1 LN2 h + b1) + b2."""
+
+    def __init__(self, index, cfg):
+        self.pre = f"layer{index}."
+        self.batch, self.seq, self.heads = cfg["batch"], cfg["seq"], cfg["heads"]
+        self.d = cfg["hidden"] // cfg["heads"]
+        self.param_names = [self.pre + n for n in (
+            "ln1.weight", "ln1.bias", "attn.qkv.weight", "attn.qkv.bias", "attn.out.weight", "attn.out.bias",
+            "ln2.weight", "ln2.bias", "ffn.w1.weight", "ffn.w1.bias", "ffn.w2.weight", "ffn.w2.bias")]
+
+    def forward(self, x, p, q, batch):
+        P = lambda n: p[self.pre + n]
+        hidden = x.shape[1]
+        u, self.ln1 = ops.layernorm_fwd(x, P("ln1.weight"), P("ln1.bias"))
+        self.u = q(u)
+        self.qkv = q(ops.linear_fwd(self.u, P("attn.qkv.weight"), P("attn.qkv.bias")))
+        qh, kh, vh = (ops.split_heads(self.qkv[:, i * hidden:(i + 1) * hidden], self.batch, self.seq, self.heads) for i in range(3))
+        scores = qh @ kh.transpose(0, 1, 3, 2) / np.sqrt(self.d)
+        self.prob = q(ops.softmax_rows(scores))
+        self.ctx = q(ops.merge_heads(self.prob @ vh))
+        self.h = q(x + ops.linear_fwd(self.ctx, P("attn.out.weight"), P("attn.out.bias")))
+        v, self.ln2 = ops.layernorm_fwd(self.h, P("ln2.weight"), P("ln2.bias"))
+        self.v = q(v)
+        z1 = ops.linear_fwd(self.v, P("ffn.w1.weight"), P("ffn.w1.bias"))
+        self.z1 = q(z1)                      # kept for the GELU derivative
+        self.f = q(ops.gelu_fwd(z1))
+        return q(self.h + ops.linear_fwd(self.f, P("ffn.w2.weight"), P("ffn.w2.bias")))
+
+    def backward(self, dout, p, q, need_input_grad):
+        P = lambda n: p[self.pre + n]
+        g = {}
+        hidden = dout.shape[1]
+        # feed-forward half
+        g[self.pre + "ffn.w2.weight"], g[self.pre + "ffn.w2.bias"], df = ops.linear_bwd(dout, self.f, P("ffn.w2.weight"), True)
+        dz1 = q(df * ops.gelu_grad(self.z1))
+        g[self.pre + "ffn.w1.weight"], g[self.pre + "ffn.w1.bias"], dv = ops.linear_bwd(dz1, self.v, P("ffn.w1.weight"), True)
+        dv = q(dv)
+        dh_ln, g[self.pre + "ln2.weight"], g[self.pre + "ln2.bias"] = ops.layernorm_bwd(dv, P("ln2.weight"), self.ln2)
+        dh = q(dout + dh_ln)                 # residual fan-in
+        # attention half
+        g[self.pre + "attn.out.weight"], g[self.pre + "attn.out.bias"], dctx = ops.linear_bwd(dh, self.ctx, P("attn.out.weight"), True)
+        dctx = q(dctx)
+        qh, kh, vh = (ops.split_heads(self.qkv[:, i * hidden:(i + 1) * hidden], self.batch, self.seq, self.heads) for i in range(3))
+        do = ops.split_heads(dctx, self.batch, self.seq, self.heads)
+        dvh = self.prob.transpose(0, 1, 3, 2) @ do
+        dprob = do @ vh.transpose(0, 1, 3, 2)
+        ds = q(self.prob * (dprob - (dprob * self.prob).sum(axis=-1, keepdims=True)) / np.sqrt(self.d))
+        dqh = ds @ kh
+        dkh = ds.transpose(0, 1, 3, 2) @ qh
+        dqkv = q(np.concatenate([ops.merge_heads(t) for t in (dqh, dkh, dvh)], axis=1))
+        g[self.pre + "attn.qkv.weight"], g[self.pre + "attn.qkv.bias"], du = ops.linear_bwd(dqkv, self.u, P("attn.qkv.weight"), True)
+        du = q(du)
+        dx_ln, g[self.pre + "ln1.weight"], g[self.pre + "ln1.bias"] = ops.layernorm_bwd(du, P("ln1.weight"), self.ln1)
+        dx = q(dh + dx_ln) if need_input_grad else None
+        return g, dx
+
+
+class MaskedHeadUnit:
+    """Final LayerNorm on the rows that carry a loss, vocabulary projection, softmax cross-entropy."""
+
+    param_names = ["head.ln.weight", "head.ln.bias", "head.vocab.weight", "head.vocab.bias"]
+
+    def forward(self, x, p, q, batch):
+        self.rows, self.n_rows_total = batch["loss_rows"], x.shape[0]
+        y, self.ln = ops.layernorm_fwd(x[self.rows], p["head.ln.weight"], p["head.ln.bias"])
+        self.y = q(y)
+        logits = ops.linear_fwd(self.y, p["head.vocab.weight"], p["head.vocab.bias"])
+        self.loss_value, self.dz = ops.softmax_ce(logits, batch["labels"])
+        return self.loss_value
+
+    def backward(self, _dout, p, q, need_input_grad):
+        g = {}
+        dz = q(self.dz)
+        g["head.vocab.weight"], g["head.vocab.bias"], dy = ops.linear_bwd(dz, self.y, p["head.vocab.weight"], True)
+        dy = q(dy)
+        dxr, g["head.ln.weight"], g["head.ln.bias"] = ops.layernorm_bwd(dy, p["head.ln.weight"], self.ln)
+        dx = None
+        if need_input_grad:
+            dx = np.zeros((self.n_rows_total, dxr.shape[1]))
+            dx[self.rows] = q(dxr)               # loss rows are distinct positions
+        return g, dx

@@ -42,6 +42,10 @@ CONFIGS = {
                            dims=[100, 72, 136, 52, 7], depths=[0, 1, 2, 3, 4]),
     "ragged_mlp_bf16": dict(family="mlp", dtype="bf16", batch=83,
                             dims=[136, 200, 72, 264, 13], depths=[0, 1, 2, 3, 4]),
+    "tiny_encoder": dict(family="encoder", dtype="bf16", batch=2, seq=4, layers=2, hidden=8, heads=2, ffn=16,
+                         vocab=11, loss_rows=3, depths=[0, 1, 2, 3, 4]),
+    "small_encoder_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=2, hidden=64, heads=4,
+                               ffn=136, vocab=203, loss_rows=17, depths=[0, 1, 2, 3, 4]),
     "one_layer_bf16": dict(family="mlp", dtype="bf16", batch=16,
                            dims=[64, 10], depths=[0, 1]),
 }

@@ -42,6 +42,25 @@ def tensor_specs(cfg: dict) -> list:
             specs.append((f"fc{i}.weight", (dims[i + 1], dims[i]), i, ("normal", (2.0 / fan_in) ** 0.5)))
             specs.append((f"fc{i}.bias", (dims[i + 1],), i, ("const", 0.0)))
         return specs
+    if fam == "encoder":
+        h, f, v, seq = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["seq"]
+        std = 0.02
+        specs.append(("embed.tok.weight", (v, h), 0, ("normal", std)))
+        specs.append(("embed.pos.weight", (seq, h), 0, ("normal", std)))
+        for i in range(cfg["layers"]):
+            u, pre = i + 1, f"layer{i}."
+            specs += [
+                (pre + "ln1.weight", (h,), u, ("const", 1.0)), (pre + "ln1.bias", (h,), u, ("const", 0.0)),
+                (pre + "attn.qkv.weight", (3 * h, h), u, ("normal", std)), (pre + "attn.qkv.bias", (3 * h,), u, ("const", 0.0)),
+                (pre + "attn.out.weight", (h, h), u, ("normal", std)), (pre + "attn.out.bias", (h,), u, ("const", 0.0)),
+                (pre + "ln2.weight", (h,), u, ("const", 1.0)), (pre + "ln2.bias", (h,), u, ("const", 0.0)),
+                (pre + "ffn.w1.weight", (f, h), u, ("normal", std)), (pre + "ffn.w1.bias", (f,), u, ("const", 0.0)),
+                (pre + "ffn.w2.weight", (h, f), u, ("normal", std)), (pre + "ffn.w2.bias", (h,), u, ("const", 0.0)),
+            ]
+        u = cfg["layers"] + 1
+        specs += [("head.ln.weight", (h,), u, ("const", 1.0)), ("head.ln.bias", (h,), u, ("const", 0.0)),
+                  ("head.vocab.weight", (v, h), u, ("normal", std)), ("head.vocab.bias", (v,), u, ("const", 0.0))]
+        return specs
     raise NotImplementedError(fam)
 
 
@@ -71,4 +90,11 @@ def make_batch(cfg: dict, seed: int = 0) -> dict:
         x = _store(_normal(seed, "batch/x", (b, d), 1.0), cfg["dtype"])
         labels = _stream(seed, "batch/labels").integers(0, c, size=(b,), dtype=np.int32)
         return {"x": x, "labels": torch.from_numpy(labels)}
+    if fam == "encoder":
+        b, seq, v, rows = cfg["batch"], cfg["seq"], cfg["vocab"], cfg["loss_rows"]
+        ids = _stream(seed, "batch/ids").integers(0, v, size=(b, seq), dtype=np.int32)
+        # the positions that carry a loss: the first `rows` of a seeded permutation of all b * seq positions
+        perm = _stream(seed, "batch/loss_rows").permutation(b * seq)[:rows].astype(np.int32)
+        labels = _stream(seed, "batch/labels").integers(0, v, size=(rows,), dtype=np.int32)
+        return {"x": torch.from_numpy(ids), "loss_rows": torch.from_numpy(perm), "labels": torch.from_numpy(labels)}
     raise NotImplementedError(fam)
