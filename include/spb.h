@@ -138,9 +138,11 @@ int spb_workspace_size(const spb_model* m, int32_t k, size_t* bytes);
 
 /* Full forward pass to the loss (Sec. 2: "performs a forward pass to obtain the loss with respect to
  * the model"), keeping only what a backward pass of depth <= stash_depth_k will read.
- *   x          device, model dtype: [batch, dims[0]] (MLP), NHWC images (CNN); int32 token ids (encoder)
+ *   x          device, model dtype: [batch, dims[0]] (MLP), NHWC images (CNN); int32 token ids [batch, seq]
+ *              in [0, vocab) (encoder).  The encoder reads the ids again in a full-depth backward pass.
  *   labels     device, int32, one class index per loss row, each in [0, classes)
- *   loss_rows  device, int32 row indices that carry a loss (encoder); NULL otherwise
+ *   loss_rows  device, int32: the loss_rows distinct positions in [0, batch * seq) that carry a loss
+ *              (encoder, read again by the backward pass); NULL otherwise
  *   workspace  device, 256-byte aligned, >= spb_workspace_size(stash_depth_k) bytes; holds the stash
  *              until the matching backward call has completed
  *   loss_out   device, one float32: mean softmax cross-entropy over the loss rows

@@ -29,6 +29,10 @@ int Model::gemm(const GemmProblem& p, hipStream_t s) {
   return check(e, p.name);
 }
 
+int Model::run(const char* name, double bytes, hipStream_t s, const std::function<hipError_t()>& launch) {
+  return check(timer.run(name, 0.0, bytes, s, launch), name);
+}
+
 KernelTimer::~KernelTimer() {
   for (auto& r : recs_) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
   for (auto e : pool_) (void)hipEventDestroy(e);
@@ -110,9 +114,9 @@ int spb_model_create(const spb_model_desc* desc, spb_model** out) {
   std::unique_ptr<spb::Model> impl;
   switch (desc->family) {
     case SPB_FAMILY_MLP: impl = spb::make_mlp(*desc); break;
+    case SPB_FAMILY_ENCODER: impl = spb::make_encoder(*desc); break;
     case SPB_FAMILY_RESNET_BASIC:
     case SPB_FAMILY_RESNET_BOTTLENECK:
-    case SPB_FAMILY_ENCODER:
       set_error("spb_model_create: family %d is not built into this library", desc->family);
       return SPB_ERR_UNSUPPORTED;
     default:
@@ -185,6 +189,7 @@ int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_
   SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_forward: null model");
   m->impl->stashed_k = -1;
   SPB_REQUIRE(x && labels && loss_out, SPB_ERR_INVALID_ARG, "spb_forward: null input, labels or loss pointer");
+  SPB_REQUIRE(!m->impl->needs_loss_rows || loss_rows, SPB_ERR_INVALID_ARG, "spb_forward: this model needs the loss_rows index array");
   SPB_REQUIRE((reinterpret_cast<uintptr_t>(x) & 15u) == 0, SPB_ERR_INVALID_ARG, "spb_forward: input is not 16-byte aligned");
   if (int rc = depth_ok(m, k, "spb_forward")) return rc;
   SPB_REQUIRE(m->impl->params_bound, SPB_ERR_STATE, "spb_forward: parameters are not bound");

@@ -301,8 +301,11 @@ hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream) {
   if (!extent_ok(p.a_layout, p.M, p.lda) || !extent_ok(p.b_layout, p.N, p.ldb)) return hipErrorInvalidValue;
   if (p.ldc < p.N) return hipErrorInvalidValue;
   if (p.epilogue == Epilogue::MaskStore && (!p.mask || p.ldmask < p.N)) return hipErrorInvalidValue;
+  if (p.dtype == DType::BF16 && gemm_dma_accepts(p)) return launch_gemm_dma(p, stream);
+  // the register-staged kernel below knows only the dense-layer epilogues of a single product
+  if (p.batch != 1 || p.alpha != 1.f || p.residual || p.aux_out || p.act == Act::Gelu || p.epilogue == Epilogue::GeluBwdStore)
+    return hipErrorInvalidValue;
   if (p.dtype == DType::F32) return launch_typed<float>(p, stream);
-  if (gemm_dma_accepts(p)) return launch_gemm_dma(p, stream);
   return launch_typed<bf16_t>(p, stream);
 }
 

@@ -38,10 +38,22 @@ __device__ __forceinline__ void store_elem(bf16_t* p, float v) {
 struct GemmParams {
   const void* A; const void* B; void* C;
   const void* bias; const void* mask; float* a_row_sum;
-  int M, N, K, lda, ldb, ldc, ldmask;
-  int epilogue, relu;
+  const void* residual; void* aux_out;
+  int M, N, K, lda, ldb, ldc, ldmask, ldres, ldaux;
+  int epilogue, act;
+  float alpha;
   int tiles_m, tiles_n;
+  BatchStride a_batch, b_batch, c_batch;
 };
+
+__device__ __forceinline__ long long batch_offset(const BatchStride& b, int z) {
+  return (long long)(z / b.inner_count) * b.outer + (long long)(z % b.inner_count) * b.inner;
+}
+
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.f + erff(x * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  return 0.5f * (1.f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
+}
 
 
 // Accumulator register r of lane l of a 32x32 MFMA block holds C[8*(r/4) + 4*(l/32) + r%4][l%32].
@@ -65,7 +77,7 @@ __device__ __forceinline__ void store_tile(const GemmParams& p, f32x16 (&acc)[TM
           static_cast<float*>(p.C)[(size_t)m * p.ldc + n] = v + bv;
         } else if (p.epilogue == (int)Epilogue::BiasAct) {
           v += bv;
-          if (p.relu) v = fmaxf(v, 0.f);
+          if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
           store_elem(static_cast<T*>(p.C) + (size_t)m * p.ldc + n, v);
         } else {
           if (!(to_float(mask[(size_t)m * p.ldmask + n]) > 0.f)) v = 0.f;
@@ -80,7 +92,10 @@ inline GemmParams make_params(const GemmProblem& q, int bm, int bn) {
   GemmParams p;
   p.A = q.A; p.B = q.B; p.C = q.C; p.bias = q.bias; p.mask = q.mask; p.a_row_sum = q.a_row_sum;
   p.M = q.M; p.N = q.N; p.K = q.K; p.lda = q.lda; p.ldb = q.ldb; p.ldc = q.ldc; p.ldmask = q.ldmask;
-  p.epilogue = (int)q.epilogue; p.relu = q.relu;
+  p.residual = q.residual; p.aux_out = q.aux_out; p.ldres = q.ldres; p.ldaux = q.ldaux;
+  p.epilogue = (int)q.epilogue; p.act = q.relu ? (int)Act::Relu : (int)q.act;
+  p.alpha = q.alpha;
+  p.a_batch = q.a_batch; p.b_batch = q.b_batch; p.c_batch = q.c_batch;
   p.tiles_m = (q.M + bm - 1) / bm;
   p.tiles_n = (q.N + bn - 1) / bn;
   return p;

@@ -145,7 +145,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // then) and reads it back row by row, so that bias, mask and result move in 16-byte pieces along n.
 template <int WM, int WN>
 __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage,
-                                                int row_base, int col_base, int lane) {
+                                                int row_base, int col_base, int lane, long long c_offset) {
   constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of rows 4 apart
 #pragma unroll
   for (int i = 0; i < WM / 32; ++i)
@@ -164,8 +164,8 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
       const int row = u / (WN / 4), c = (u % (WN / 4)) * 4;
       const int m = row_base + row, n = col_base + c;
       if (m >= p.M || n >= p.N) continue;
-      f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
-      float* dst = static_cast<float*>(p.C) + (size_t)m * p.ldc + n;
+      f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c) * p.alpha;
+      float* dst = static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n;
       if (n + 4 <= p.N) {
         if (bias) {
           const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
@@ -179,48 +179,62 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
     }
   } else {
     constexpr int kUnits = WM * WN / 8;
-    const bool masked = p.epilogue == (int)Epilogue::MaskStore;
+    const int mode = p.epilogue;  // BiasAct, MaskStore or GeluBwdStore
     const bf16_t* mask = static_cast<const bf16_t*>(p.mask);
+    const bf16_t* res = static_cast<const bf16_t*>(p.residual);
+    bf16_t* aux = static_cast<bf16_t*>(p.aux_out);
+    auto unpack = [](const u32x4& w, float (&f)[8]) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
+    };
+    auto pack = [](const float (&f)[8]) {
+      u32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) o[d] = pack_bf16(f[2 * d], f[2 * d + 1]);
+      return o;
+    };
+    // one element of the epilogue, shared by the 16-byte path and the ragged tail
+    auto finish = [&](float v, float b, float mk, float r, float& pre) {
+      if (mode == (int)Epilogue::MaskStore) return mk > 0.f ? v : 0.f;
+      if (mode == (int)Epilogue::GeluBwdStore) return v * gelu_grad_f(mk);
+      v = v * p.alpha + b;
+      pre = v;
+      if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
+      else if (p.act == (int)Act::Gelu) v = gelu_f(v);
+      return v + r;
+    };
 #pragma unroll
     for (int it = 0; it < kUnits / 64; ++it) {
       const int u = it * 64 + lane;
       const int row = u / (WN / 8), c = (u % (WN / 8)) * 8;
       const int m = row_base + row, n = col_base + c;
       if (m >= p.M || n >= p.N) continue;
-      float v[8];
+      float v[8], b[8], mk[8], r[8], pre[8];
       const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
       const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
 #pragma unroll
       for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
-      bf16_t* dst = static_cast<bf16_t*>(p.C) + (size_t)m * p.ldc + n;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { b[e] = 0.f; mk[e] = 0.f; r[e] = 0.f; pre[e] = 0.f; }
+      bf16_t* dst = static_cast<bf16_t*>(p.C) + c_offset + (size_t)m * p.ldc + n;
       if (n + 8 <= p.N) {
-        if (masked) {
-          const u32x4 mk = *reinterpret_cast<const u32x4*>(mask + (size_t)m * p.ldmask + n);
-#pragma unroll
-          for (int d = 0; d < 4; ++d) {
-            if (!(__uint_as_float(mk[d] << 16) > 0.f)) v[2 * d] = 0.f;
-            if (!(__uint_as_float(mk[d] & 0xFFFF0000u) > 0.f)) v[2 * d + 1] = 0.f;
-          }
+        if (mode != (int)Epilogue::BiasAct) {
+          unpack(*reinterpret_cast<const u32x4*>(mask + (size_t)m * p.ldmask + n), mk);
         } else {
-          if (bias) {
-            const u32x4 bb = *reinterpret_cast<const u32x4*>(bias + n);
-#pragma unroll
-            for (int d = 0; d < 4; ++d) { v[2 * d] += __uint_as_float(bb[d] << 16); v[2 * d + 1] += __uint_as_float(bb[d] & 0xFFFF0000u); }
-          }
-          if (p.relu) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
-          }
+          if (bias) unpack(*reinterpret_cast<const u32x4*>(bias + n), b);
+          if (res) unpack(*reinterpret_cast<const u32x4*>(res + (size_t)m * p.ldres + n), r);
         }
-        u32x4 o;
 #pragma unroll
-        for (int d = 0; d < 4; ++d) o[d] = pack_bf16(v[2 * d], v[2 * d + 1]);
-        *reinterpret_cast<u32x4*>(dst) = o;
+        for (int e = 0; e < 8; ++e) v[e] = finish(v[e], b[e], mk[e], r[e], pre[e]);
+        if (aux && mode == (int)Epilogue::BiasAct) *reinterpret_cast<u32x4*>(aux + (size_t)m * p.ldaux + n) = pack(pre);
+        *reinterpret_cast<u32x4*>(dst) = pack(v);
       } else {
         for (int e = 0; e < 8 && n + e < p.N; ++e) {
-          float x = v[e];
-          if (masked) { if (!(to_float(mask[(size_t)m * p.ldmask + n + e]) > 0.f)) x = 0.f; }
-          else { if (bias) x += to_float(bias[n + e]); if (p.relu) x = fmaxf(x, 0.f); }
+          float be = 0.f, me = 0.f, re = 0.f, pe = 0.f;
+          if (mode != (int)Epilogue::BiasAct) me = to_float(mask[(size_t)m * p.ldmask + n + e]);
+          else { if (bias) be = to_float(bias[n + e]); if (res) re = to_float(res[(size_t)m * p.ldres + n + e]); }
+          const float x = finish(v[e], be, me, re, pe);
+          if (aux && mode == (int)Epilogue::BiasAct) store_elem(aux + (size_t)m * p.ldaux + n + e, pe);
           store_elem(dst + e, x);
         }
       }
@@ -251,8 +265,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 
   TileSource<BM, LA, NW> src_a;
   TileSource<BN, LB, NW> src_b;
-  src_a.init(static_cast<const bf16_t*>(p.A), p.lda, m0, p.M, wave, lane);
-  src_b.init(static_cast<const bf16_t*>(p.B), p.ldb, n0, p.N, wave, lane);
+  const int z = blockIdx.y;  // batch entry
+  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset(p.a_batch, z), p.lda, m0, p.M, wave, lane);
+  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset(p.b_batch, z), p.ldb, n0, p.N, wave, lane);
   const int n_steps = (p.K + kTileK - 1) / kTileK;
   auto issue = [&](int t) {
     char* stage = lds + (t % STAGES) * kStageBytes;
@@ -322,7 +337,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   if (want_row_sum && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = row_sum;
   wait_loads_and_barrier<0>();  // every wave is done with the tile ring
   float* stage = reinterpret_cast<float*>(lds) + wave * (WM * (WN + 4));
-  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane);
+  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset(p.c_batch, z));
 }
 
 template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
@@ -339,13 +354,13 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
       raised = true;
     }
   }
-  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, q.batch), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
 template <Layout LA, Layout LB>
 hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
-  const long big_tiles = (long)((q.M + 127) / 128) * ((q.N + 127) / 128);
+  const long big_tiles = (long)((q.M + 127) / 128) * ((q.N + 127) / 128) * q.batch;
   if (big_tiles >= 192) return launch_tile<128, 128, 3, 2, 2, LA, LB>(q, stream);
   return launch_tile<64, 64, 4, 2, 2, LA, LB>(q, stream);
 }
@@ -363,7 +378,14 @@ bool gemm_dma_accepts(const GemmProblem& p) {
   const int per_out = p.epilogue == Epilogue::StoreF32 ? 4 : 8;
   if (p.ldc % per_out || !a16(p.C)) return false;
   if (p.bias && !a16(p.bias)) return false;
-  if (p.epilogue == Epilogue::MaskStore && (p.ldmask % 8 || !a16(p.mask))) return false;
+  const bool reads_mask = p.epilogue == Epilogue::MaskStore || p.epilogue == Epilogue::GeluBwdStore;
+  if (reads_mask && (!p.mask || p.ldmask % 8 || !a16(p.mask))) return false;
+  if (p.residual && (p.ldres % 8 || !a16(p.residual))) return false;
+  if (p.aux_out && (p.ldaux % 8 || !a16(p.aux_out))) return false;
+  if (p.batch < 1 || p.batch > 65535 || (p.batch > 1 && p.a_row_sum)) return false;
+  // batch offsets must keep every operand 16-byte aligned
+  for (const BatchStride* b : {&p.a_batch, &p.b_batch, &p.c_batch})
+    if (b->inner_count < 1 || b->outer % 8 || b->inner % 8) return false;
   return true;
 }
 

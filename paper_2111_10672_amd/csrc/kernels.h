@@ -17,9 +17,18 @@ enum class Layout : int {
 };
 
 enum class Epilogue : int {
-  StoreF32 = 0,      // C float32 = acc (+ bias[n])
-  BiasAct = 1,       // C (T) = act(acc + bias[n]); act = ReLU if relu else identity
-  MaskStore = 2,     // C (T) = mask[m, n] > 0 ? acc : 0   (ReLU backward fused into the input-gradient product)
+  StoreF32 = 0,      // C float32 = alpha * acc (+ bias[n])
+  BiasAct = 1,       // v = alpha * acc + bias[n]; aux_out (T) = v if given; C (T) = act(v) (+ residual[m, n])
+  MaskStore = 2,     // C (T) = mask[m, n] > 0 ? acc : 0          (ReLU backward fused into the input-gradient product)
+  GeluBwdStore = 3,  // C (T) = acc * gelu'(mask[m, n])           (GELU backward; mask holds the pre-activation)
+};
+
+enum class Act : int { None = 0, Relu = 1, Gelu = 2 };
+
+// Element offset of batch entry z of an operand: (z / inner_count) * outer + (z % inner_count) * inner.
+struct BatchStride {
+  long long outer = 0, inner = 0;
+  int inner_count = 1;
 };
 
 struct GemmProblem {
@@ -31,7 +40,13 @@ struct GemmProblem {
   const void* B = nullptr; int ldb = 0;
   void* C = nullptr; int ldc = 0;
   const void* bias = nullptr;     // [N], dtype
-  int relu = 0;
+  int relu = 0;                   // shorthand for act = Relu
+  Act act = Act::None;
+  float alpha = 1.f;
+  const void* residual = nullptr; int ldres = 0;   // [M, N], dtype, added after the activation (BiasAct)
+  void* aux_out = nullptr; int ldaux = 0;          // [M, N], dtype, receives the pre-activation (BiasAct)
+  int batch = 1;                  // independent products launched together (attention heads)
+  BatchStride a_batch, b_batch, c_batch;
   const void* mask = nullptr; int ldmask = 0;   // [M, N], dtype
   // The buffer's owner keeps zeros between the end of each row's data and the next multiple of 8 elements
   // along the contiguous index (lets a kernel fetch whole 16-byte chunks).
@@ -58,4 +73,26 @@ hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labe
 
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
 
+// ---- row-wise kernels of the encoder units (bfloat16 rows of `width` elements, width % 8 == 0, <= 2048) ----
+// y[r] = LayerNorm(x[rows ? rows[r] : r]) for r < n_rows; stats[r] = (mean, 1 / sqrt(var + 1e-5)).
+hipError_t launch_layernorm_fwd(const void* x, int ldx, const int32_t* rows, int n_rows, int width, const void* gamma, const void* beta,
+                                void* y, int ldy, float* stats, hipStream_t s);
+// LayerNorm backward.  dy and stats are indexed by r, x and dx by rows ? rows[r] : r.  dx (optional) receives the input
+// gradient plus res[r] (optional).  dgamma/dbeta (float32 [width]) are overwritten; partial is scratch of
+// layernorm_partial_floats(n_rows, width) floats.
+size_t layernorm_partial_floats(int n_rows, int width);
+hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx, const int32_t* rows, const float* stats,
+                                const void* gamma, const void* res, int ldres, void* dx, int lddx, float* partial,
+                                float* dgamma, float* dbeta, int n_rows, int width, hipStream_t s);
+// prob (bfloat16) = softmax of each row of scores (float32), rows of `len` contiguous entries.
+hipError_t launch_softmax_fwd(const float* scores, void* prob, long long n_rows, int len, hipStream_t s);
+// dscore (bfloat16) = prob * (dprob - sum(dprob * prob)) * scale per row.
+hipError_t launch_softmax_bwd(const float* dprob, const void* prob, void* dscore, long long n_rows, int len, float scale, hipStream_t s);
+// out[m] = tok[ids[m]] + pos[m % seq];  gradients: dtok (float32 [vocab, width], overwritten), dpos (float32 [seq, width]).
+hipError_t launch_embedding_fwd(const int32_t* ids, const void* tok, const void* pos, void* out, int ldo, int n_rows, int seq, int vocab,
+                                int width, hipStream_t s);
+hipError_t launch_embedding_bwd(const int32_t* ids, const void* dx, int lddx, float* dtok, float* dpos, int batch, int seq, int vocab,
+                                int width, hipStream_t s);
+
 }  // namespace spb
+

@@ -57,16 +57,19 @@ class Model {
   std::vector<ParamInfo> params;
   std::vector<void*> param_ptrs, grad_ptrs;
   bool params_bound = false, grads_bound = false;
+  bool needs_loss_rows = false;
   int stashed_k = -1;  // depth the last forward pass stashed for; -1 = no forward yet
   void* ws = nullptr;
   KernelTimer timer;
 
  protected:
   int gemm(const GemmProblem& p, hipStream_t s);
+  int run(const char* name, double bytes, hipStream_t s, const std::function<hipError_t()>& launch);
   int check(hipError_t e, const char* what);
 };
 
 std::unique_ptr<Model> make_mlp(const spb_model_desc& d);
+std::unique_ptr<Model> make_encoder(const spb_model_desc& d);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

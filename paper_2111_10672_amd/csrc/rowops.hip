@@ -1,0 +1,352 @@
+// Row-wise, memory-bound kernels of the Transformer-encoder units: LayerNorm forward and backward, the
+// softmax of attention and its backward, embedding lookup and its gradient.  Each row is handled by one
+// wavefront (64 lanes), values move as 16-byte chunks of 8 bfloat16, reductions use wavefront shuffles.
+// Reductions over rows (LayerNorm scale/shift gradients) are done in two fixed-order stages so that a
+// step gives the same bits on every run.
+#include "kernels.h"
+
+namespace spb {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxChunks = 4;  // 16-byte chunks per lane: rows of up to 64 * 4 * 8 = 2048 elements
+constexpr float kLnEps = 1e-5f;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ void unpack8(const u32x4& w, float (&f)[8]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
+}
+__device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
+  u32x4 o;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) o[d] = pack2(f[2 * d], f[2 * d + 1]);
+  return o;
+}
+__device__ __forceinline__ uint16_t to_bf16(float v) {
+  uint32_t u = __float_as_uint(v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// y[r] = gamma * (x[src(r)] - mean) * rstd + beta;  stats[r] = (mean, rstd).  src(r) = rows ? rows[r] : r.
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const uint16_t* __restrict__ x, int ldx, const int32_t* __restrict__ rows,
+                                                            int n_rows, int width, const uint16_t* __restrict__ gamma,
+                                                            const uint16_t* __restrict__ beta, uint16_t* __restrict__ y, int ldy,
+                                                            float* __restrict__ stats) {
+  const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  const int chunks = width >> 3;
+  const uint16_t* src = x + (size_t)(rows ? rows[r] : r) * ldx;
+  float v[kMaxChunks][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < kMaxChunks; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+      unpack8(*reinterpret_cast<const u32x4*>(src + c * 8), v[i]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += v[i][e];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)width;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < kMaxChunks; ++i)
+    if (lane + 64 * i < chunks) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d = v[i][e] - mean; sq += d * d; }
+    }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)width + kLnEps);
+#pragma unroll
+  for (int i = 0; i < kMaxChunks; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+      float g[8], b[8], o[8];
+      unpack8(*reinterpret_cast<const u32x4*>(gamma + c * 8), g);
+      unpack8(*reinterpret_cast<const u32x4*>(beta + c * 8), b);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = g[e] * ((v[i][e] - mean) * rstd) + b[e];
+      *reinterpret_cast<u32x4*>(y + (size_t)r * ldy + c * 8) = pack8(o);
+    }
+  }
+  if (lane == 0) { stats[2 * r] = mean; stats[2 * r + 1] = rstd; }
+}
+
+// LayerNorm backward for rows r0 .. r0+31 of this workgroup (8 per wavefront):
+//   g = dy * gamma;  dx = (g - mean(g) - xhat * mean(g * xhat)) * rstd (+ res);  partial sums of dy * xhat and dy per column.
+constexpr int kLnRowsPerBlock = 32;
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const uint16_t* __restrict__ dy, int lddy, const uint16_t* __restrict__ x,
+                                                            int ldx, const int32_t* __restrict__ rows, const float* __restrict__ stats,
+                                                            const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ res, int ldres,
+                                                            uint16_t* __restrict__ dx, int lddx, float* __restrict__ partial,
+                                                            int n_rows, int width) {
+  extern __shared__ float sh[];  // [2][width]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunks = width >> 3;
+  float dgam[kMaxChunks][8], dbet[kMaxChunks][8], gam[kMaxChunks][8];
+#pragma unroll
+  for (int i = 0; i < kMaxChunks; ++i) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dgam[i][e] = 0.f; dbet[i][e] = 0.f; gam[i][e] = 0.f; }
+    if (lane + 64 * i < chunks) unpack8(*reinterpret_cast<const u32x4*>(gamma + (lane + 64 * i) * 8), gam[i]);
+  }
+  for (int j = 0; j < kLnRowsPerBlock / 4; ++j) {
+    const int r = blockIdx.x * kLnRowsPerBlock + wave * (kLnRowsPerBlock / 4) + j;
+    if (r >= n_rows) break;
+    const size_t xr = rows ? rows[r] : r;
+    const float mean = stats[2 * r], rstd = stats[2 * r + 1];
+    float g[kMaxChunks][8], xh[kMaxChunks][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i) {
+      const int c = lane + 64 * i;
+      if (c < chunks) {
+        float d[8], xv[8];
+        unpack8(*reinterpret_cast<const u32x4*>(dy + (size_t)r * lddy + c * 8), d);
+        unpack8(*reinterpret_cast<const u32x4*>(x + xr * ldx + c * 8), xv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          xh[i][e] = (xv[e] - mean) * rstd;
+          g[i][e] = d[e] * gam[i][e];
+          s1 += g[i][e];
+          s2 += g[i][e] * xh[i][e];
+          dgam[i][e] += d[e] * xh[i][e];
+          dbet[i][e] += d[e];
+        }
+      }
+    }
+    if (dx) {
+      const float m1 = wave_sum(s1) / (float)width, m2 = wave_sum(s2) / (float)width;
+#pragma unroll
+      for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = lane + 64 * i;
+        if (c < chunks) {
+          float o[8], rv[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) rv[e] = 0.f;
+          if (res) unpack8(*reinterpret_cast<const u32x4*>(res + (size_t)r * ldres + c * 8), rv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (g[i][e] - m1 - xh[i][e] * m2) * rstd + rv[e];
+          *reinterpret_cast<u32x4*>(dx + xr * lddx + c * 8) = pack8(o);
+        }
+      }
+    }
+  }
+  // add the four wavefronts' column sums in wavefront order
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = lane + 64 * i;
+        if (c < chunks) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int col = c * 8 + e;
+            sh[col] = (w == 0 ? 0.f : sh[col]) + dgam[i][e];
+            sh[width + col] = (w == 0 ? 0.f : sh[width + col]) + dbet[i][e];
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int col = threadIdx.x; col < 2 * width; col += 256) partial[(size_t)blockIdx.x * 2 * width + col] = sh[col];
+}
+
+// out_a[c] = sum_b partial[b][0][c];  out_b[c] = sum_b partial[b][1][c], blocks added in index order.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int n_blocks, int width,
+                                                              float* __restrict__ out_a, float* __restrict__ out_b) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= 2 * width) return;
+  float s = 0.f;
+  for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * 2 * width + col];
+  if (col < width) out_a[col] = s;
+  else out_b[col - width] = s;
+}
+
+// p[r, :] = softmax(s[r, :]) in bfloat16; one wavefront per row.
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restrict__ s, uint16_t* __restrict__ p, long long n_rows, int len) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  const float* in = s + r * len;
+  float m = -INFINITY;
+  for (int c = lane; c < len; c += 64) m = fmaxf(m, in[c]);
+  m = wave_max(m);
+  float z = 0.f;
+  for (int c = lane; c < len; c += 64) z += expf(in[c] - m);
+  const float inv = 1.f / wave_sum(z);
+  for (int c = lane; c < len; c += 64) p[r * len + c] = to_bf16(expf(in[c] - m) * inv);
+}
+
+// ds[r, :] = p * (dp - sum(dp * p)) * scale in bfloat16; one wavefront per row.
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* __restrict__ dp, const uint16_t* __restrict__ p,
+                                                          uint16_t* __restrict__ ds, long long n_rows, int len, float scale) {
+  const int lane = threadIdx.x & 63;
+  const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= n_rows) return;
+  float dot = 0.f;
+  for (int c = lane; c < len; c += 64) dot += dp[r * len + c] * __uint_as_float(((uint32_t)p[r * len + c]) << 16);
+  dot = wave_sum(dot);
+  for (int c = lane; c < len; c += 64) {
+    const float pv = __uint_as_float(((uint32_t)p[r * len + c]) << 16);
+    ds[r * len + c] = to_bf16(pv * (dp[r * len + c] - dot) * scale);
+  }
+}
+
+// x0[m, :] = tok[ids[m], :] + pos[m % seq, :].  An id outside [0, vocab) is clamped into range.
+__global__ __launch_bounds__(256) void embedding_fwd_kernel(const int32_t* __restrict__ ids, const uint16_t* __restrict__ tok,
+                                                            const uint16_t* __restrict__ pos, uint16_t* __restrict__ out, int ldo,
+                                                            int n_rows, int seq, int vocab, int width) {
+  const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (m >= n_rows) return;
+  const int id = min(max(ids[m], 0), vocab - 1);
+  const uint16_t* t = tok + (size_t)id * width;
+  const uint16_t* q = pos + (size_t)(m % seq) * width;
+  for (int c = lane; c < (width >> 3); c += 64) {
+    float a[8], b[8];
+    unpack8(*reinterpret_cast<const u32x4*>(t + c * 8), a);
+    unpack8(*reinterpret_cast<const u32x4*>(q + c * 8), b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] += b[e];
+    *reinterpret_cast<u32x4*>(out + (size_t)m * ldo + c * 8) = pack8(a);
+  }
+}
+
+// Token-table gradient without atomics: the workgroup of position m does nothing unless m is the first
+// position with its token id; then it adds the rows of every position with that id, in position order.
+__global__ __launch_bounds__(256) void embedding_bwd_tok_kernel(const int32_t* __restrict__ ids, const uint16_t* __restrict__ dx, int lddx,
+                                                                float* __restrict__ dtok, int n_rows, int vocab, int width) {
+  __shared__ int flags[256];
+  __shared__ int earlier;
+  const int m = blockIdx.x, tid = threadIdx.x;
+  const int id = min(max(ids[m], 0), vocab - 1);
+  if (tid == 0) earlier = 0;
+  __syncthreads();
+  int found = 0;
+  for (int j = tid; j < m; j += 256) found |= (min(max(ids[j], 0), vocab - 1) == id);
+  if (found) earlier = 1;  // benign race: every writer stores 1
+  __syncthreads();
+  if (earlier) return;
+  constexpr int kCols = 8;  // columns per thread: width <= 2048
+  float acc[kCols];
+#pragma unroll
+  for (int i = 0; i < kCols; ++i) acc[i] = 0.f;
+  for (int base = m - (m % 256); base < n_rows; base += 256) {
+    const int j = base + tid;
+    flags[tid] = j >= m && j < n_rows && min(max(ids[j], 0), vocab - 1) == id;
+    __syncthreads();
+    for (int t = 0; t < 256; ++t) {
+      if (!flags[t]) continue;  // uniform across the workgroup
+#pragma unroll
+      for (int i = 0; i < kCols; ++i) {
+        const int c = tid + 256 * i;
+        if (c < width) acc[i] += __uint_as_float(((uint32_t)dx[(size_t)(base + t) * lddx + c]) << 16);
+      }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < kCols; ++i) {
+    const int c = tid + 256 * i;
+    if (c < width) dtok[(size_t)id * width + c] = acc[i];
+  }
+}
+
+// dpos[s, :] = sum over the batch of dx[b * seq + s, :], batch entries added in order.
+__global__ __launch_bounds__(256) void embedding_bwd_pos_kernel(const uint16_t* __restrict__ dx, int lddx, float* __restrict__ dpos,
+                                                                int batch, int seq, int width) {
+  const int s = blockIdx.x;
+  for (int c = threadIdx.x; c < width; c += 256) {
+    float acc = 0.f;
+    for (int b = 0; b < batch; ++b) acc += __uint_as_float(((uint32_t)dx[(size_t)(b * seq + s) * lddx + c]) << 16);
+    dpos[(size_t)s * width + c] = acc;
+  }
+}
+
+bool row_ok(int width, int ld) { return width > 0 && width % 8 == 0 && width <= 64 * kMaxChunks * 8 && ld >= width && ld % 8 == 0; }
+bool a16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+size_t layernorm_partial_floats(int n_rows, int width) {
+  return (size_t)((n_rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock) * 2 * width;
+}
+
+hipError_t launch_layernorm_fwd(const void* x, int ldx, const int32_t* rows, int n_rows, int width, const void* gamma, const void* beta,
+                                void* y, int ldy, float* stats, hipStream_t s) {
+  if (!x || !gamma || !beta || !y || !stats || n_rows <= 0 || !row_ok(width, ldx) || !row_ok(width, ldy)) return hipErrorInvalidValue;
+  if (!a16(x) || !a16(y) || !a16(gamma) || !a16(beta)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, s, (const uint16_t*)x, ldx, rows, n_rows, width,
+                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)y, ldy, stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx, const int32_t* rows, const float* stats,
+                                const void* gamma, const void* res, int ldres, void* dx, int lddx, float* partial,
+                                float* dgamma, float* dbeta, int n_rows, int width, hipStream_t s) {
+  if (!dy || !x || !stats || !gamma || !partial || !dgamma || !dbeta || n_rows <= 0) return hipErrorInvalidValue;
+  if (!row_ok(width, lddy) || !row_ok(width, ldx) || (dx && !row_ok(width, lddx)) || (res && !row_ok(width, ldres))) return hipErrorInvalidValue;
+  if (!a16(dy) || !a16(x) || !a16(gamma) || !a16(dx) || !a16(res)) return hipErrorInvalidValue;
+  const int blocks = (n_rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
+  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(blocks), dim3(256), (size_t)2 * width * sizeof(float), s, (const uint16_t*)dy, lddy,
+                     (const uint16_t*)x, ldx, rows, stats, (const uint16_t*)gamma, (const uint16_t*)res, ldres, (uint16_t*)dx, lddx,
+                     partial, n_rows, width);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 255) / 256), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_fwd(const float* scores, void* prob, long long n_rows, int len, hipStream_t s) {
+  if (!scores || !prob || n_rows <= 0 || len <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(softmax_fwd_kernel, dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, s, scores, (uint16_t*)prob, n_rows, len);
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_bwd(const float* dprob, const void* prob, void* dscore, long long n_rows, int len, float scale, hipStream_t s) {
+  if (!dprob || !prob || !dscore || n_rows <= 0 || len <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(softmax_bwd_kernel, dim3((unsigned)((n_rows + 3) / 4)), dim3(256), 0, s, dprob, (const uint16_t*)prob, (uint16_t*)dscore,
+                     n_rows, len, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_embedding_fwd(const int32_t* ids, const void* tok, const void* pos, void* out, int ldo, int n_rows, int seq, int vocab,
+                                int width, hipStream_t s) {
+  if (!ids || !tok || !pos || !out || n_rows <= 0 || seq <= 0 || vocab <= 0 || !row_ok(width, ldo) || !a16(tok) || !a16(pos) || !a16(out))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(embedding_fwd_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, s, ids, (const uint16_t*)tok, (const uint16_t*)pos,
+                     (uint16_t*)out, ldo, n_rows, seq, vocab, width);
+  return hipGetLastError();
+}
+
+hipError_t launch_embedding_bwd(const int32_t* ids, const void* dx, int lddx, float* dtok, float* dpos, int batch, int seq, int vocab,
+                                int width, hipStream_t s) {
+  if (!ids || !dx || !dtok || !dpos || batch <= 0 || seq <= 0 || vocab <= 0 || width <= 0 || width > 2048 || lddx < width) return hipErrorInvalidValue;
+  hipError_t e = launch_fill_zero(dtok, (size_t)vocab * width * 4, s);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(embedding_bwd_tok_kernel, dim3(batch * seq), dim3(256), 0, s, ids, (const uint16_t*)dx, lddx, dtok, batch * seq, vocab, width);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(embedding_bwd_pos_kernel, dim3(seq), dim3(256), 0, s, (const uint16_t*)dx, lddx, dpos, batch, seq, width);
+  return hipGetLastError();
+}
+
+}  // namespace spb
