@@ -51,6 +51,10 @@ def build_units(cfg):
     if fam == "mlp":
         n = len(cfg["dims"]) - 1
         return [LinearUnit(i, relu=(i < n - 1), loss=(i == n - 1)) for i in range(n)]
+    if fam in ("resnet_basic", "resnet_bottleneck"):
+        from workloads import resnet_layout
+        lay = resnet_layout(cfg)
+        return [StemUnit(lay)] + [ResidualUnit(b, lay["bottleneck"]) for b in lay["blocks"]] + [PooledHeadUnit()]
     if fam == "encoder":
         return [EmbeddingUnit(cfg)] + [EncoderLayerUnit(i, cfg) for i in range(cfg["layers"])] + [MaskedHeadUnit()]
     raise NotImplementedError(fam)
@@ -194,3 +198,108 @@ class MaskedHeadUnit:
             dx = np.zeros((self.n_rows_total, dxr.shape[1]))
             dx[self.rows] = q(dxr)               # loss rows are distinct positions
         return g, dx
+
+
+# ---- residual CNNs ------------------------------------------------------------------------------------
+
+class _ConvAffine:
+    """conv -> per-channel affine, shared by the CNN units.  Keeps the rounded pre-affine output for the scale gradient."""
+
+    def __init__(self, name_conv, name_aff, kernel, stride, pad):
+        self.w, self.scale, self.shift = name_conv + ".weight", name_aff + ".scale", name_aff + ".shift"
+        self.kernel, self.stride, self.pad = kernel, stride, pad
+        self.param_names = [self.w, self.scale, self.shift]
+
+    def forward(self, x, p, q):
+        self.x = x
+        y = ops.conv_fwd(x, p[self.w], self.stride, self.pad)
+        self.y = q(y)
+        return ops.affine_fwd(y, p[self.scale], p[self.shift])          # not yet rounded: the caller adds and activates first
+
+    def backward(self, dz, p, q, need_dx):
+        """dz: gradient at the affine's output (already masked by the activation that followed)."""
+        dy, dscale, dshift = ops.affine_bwd(dz, self.y, p[self.scale])
+        dy = q(dy)
+        g = {self.w: ops.conv_wgrad(self.x, dy, self.kernel, self.stride, self.pad), self.scale: dscale, self.shift: dshift}
+        dx = ops.conv_dgrad(dy, p[self.w], self.x.shape[1:3], self.stride, self.pad) if need_dx else None
+        return g, dx
+
+
+class StemUnit:
+    def __init__(self, lay):
+        st = lay["stem"]
+        self.conv = _ConvAffine("stem.conv", "stem.aff", st["kernel"], st["stride"], st["pad"])
+        self.pool = st["pool"]
+        self.param_names = self.conv.param_names
+
+    def forward(self, x, p, q, batch):
+        self.a = q(ops.relu_fwd(self.conv.forward(x, p, q)))
+        if not self.pool:
+            return self.a
+        out, self.arg = ops.maxpool3x3s2_fwd(self.a)
+        return out
+
+    def backward(self, dout, p, q, need_input_grad):
+        da = q(ops.maxpool3x3s2_bwd(dout, self.arg, self.a.shape[1:3])) if self.pool else dout
+        g, _ = self.conv.backward(da * (self.a > 0), p, q, False)   # the stem is the lowest unit: no input gradient
+        return g, None
+
+
+class ResidualUnit:
+    """Basic block (3x3, 3x3) or bottleneck (1x1, 3x3 carrying the stride, 1x1): out = relu(main(x) + shortcut(x))."""
+
+    def __init__(self, blk, bottleneck):
+        pre = f"block{blk['index']}."
+        if bottleneck:
+            spec = [(1, 1, 0), (3, blk["stride"], 1), (1, 1, 0)]
+        else:
+            spec = [(3, blk["stride"], 1), (3, 1, 1)]
+        self.convs = [_ConvAffine(f"{pre}conv{j}", f"{pre}aff{j}", k, s, pd) for j, (k, s, pd) in enumerate(spec, start=1)]
+        self.proj = _ConvAffine(pre + "proj", pre + "projaff", 1, blk["stride"], 0) if blk["proj"] else None
+        self.param_names = [n for c in self.convs for n in c.param_names] + (self.proj.param_names if self.proj else [])
+
+    def forward(self, x, p, q, batch):
+        shortcut = q(self.proj.forward(x, p, q)) if self.proj else x
+        h = x
+        self.acts = []
+        for conv in self.convs[:-1]:
+            h = q(ops.relu_fwd(conv.forward(h, p, q)))
+            self.acts.append(h)
+        self.out = q(ops.relu_fwd(self.convs[-1].forward(h, p, q) + shortcut))
+        return self.out
+
+    def backward(self, dout, p, q, need_input_grad):
+        g = {}
+        dsum = dout * (self.out > 0)                  # flows into both branches of the add
+        d = dsum
+        for j in range(len(self.convs) - 1, -1, -1):
+            first = j == 0
+            gj, dx = self.convs[j].backward(d, p, q, need_dx=(not first) or need_input_grad)
+            g.update(gj)
+            if not first:
+                d = q(dx) * (self.acts[j - 1] > 0)
+        dx_main = dx
+        if self.proj:
+            gp, dx_sc = self.proj.backward(dsum, p, q, need_input_grad)
+            g.update(gp)
+            dx_sc = q(dx_sc) if need_input_grad else None
+        else:
+            dx_sc = dsum
+        return g, (q(dx_main + dx_sc) if need_input_grad else None)
+
+
+class PooledHeadUnit:
+    param_names = ["head.fc.weight", "head.fc.bias"]
+
+    def forward(self, x, p, q, batch):
+        self.hw = x.shape[1:3]
+        self.pooled = q(ops.avgpool_fwd(x))
+        logits = ops.linear_fwd(self.pooled, p["head.fc.weight"], p["head.fc.bias"])
+        self.loss_value, self.dz = ops.softmax_ce(logits, batch["labels"])
+        return self.loss_value
+
+    def backward(self, _dout, p, q, need_input_grad):
+        dz = q(self.dz)
+        dw, db, dp = ops.linear_bwd(dz, self.pooled, p["head.fc.weight"], need_input_grad)
+        dx = q(ops.avgpool_bwd(q(dp), self.hw)) if need_input_grad else None
+        return {"head.fc.weight": dw, "head.fc.bias": db}, dx

@@ -278,14 +278,16 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
-double gemm_flops(const GemmProblem& p) { return 2.0 * p.M * p.N * p.K; }
+double gemm_flops(const GemmProblem& p) { return 2.0 * p.M * p.N * p.K * p.batch; }
 
 double gemm_bytes(const GemmProblem& p) {
   const double es = (double)dtype_size(p.dtype);
   const double out = p.epilogue == Epilogue::StoreF32 ? 4.0 : es;
   double b = es * ((double)p.M * p.K + (double)p.N * p.K) + out * (double)p.M * p.N;
   if (p.mask) b += es * (double)p.M * p.N;
-  return b;
+  if (p.residual) b += es * (double)p.M * p.N;
+  if (p.aux_out) b += es * (double)p.M * p.N;
+  return b * p.batch;
 }
 
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream) {

@@ -141,28 +141,29 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return (a >> 16) | (b & 0xFFFF0000u);
 }
 
-// Epilogue.  Each wave parks its WM x WN accumulator tile in its own LDS region (the tile ring is dead by
-// then) and reads it back row by row, so that bias, mask and result move in 16-byte pieces along n.
+// Epilogue.  Each wave parks 32 rows of its WM x WN accumulator tile at a time in its own LDS region (the tile
+// ring is dead by then) and reads them back row by row, so that bias, mask and result move in 16-byte pieces
+// along n.  LDS operations of one wave complete in order, so the pieces need no barrier between them.
 template <int WM, int WN>
 __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage,
                                                 int row_base, int col_base, int lane, long long c_offset) {
   constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of rows 4 apart
-#pragma unroll
-  for (int i = 0; i < WM / 32; ++i)
-#pragma unroll
-    for (int j = 0; j < WN / 32; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[i][j][r];
-  // same wave wrote and reads: LDS operations of one wave complete in order
   const bf16_t* bias = static_cast<const bf16_t*>(p.bias);
+#pragma unroll
+  for (int piece = 0; piece < WM / 32; ++piece) {
+  const int piece_row = row_base + piece * 32;
+#pragma unroll
+  for (int j = 0; j < WN / 32; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[piece][j][r];
   if (p.epilogue == (int)Epilogue::StoreF32) {
-    constexpr int kUnits = WM * WN / 4;
+    constexpr int kUnits = 32 * WN / 4;
 #pragma unroll
     for (int it = 0; it < kUnits / 64; ++it) {
       const int u = it * 64 + lane;
       const int row = u / (WN / 4), c = (u % (WN / 4)) * 4;
-      const int m = row_base + row, n = col_base + c;
+      const int m = piece_row + row, n = col_base + c;
       if (m >= p.M || n >= p.N) continue;
       f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c) * p.alpha;
       float* dst = static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n;
@@ -178,7 +179,7 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
       }
     }
   } else {
-    constexpr int kUnits = WM * WN / 8;
+    constexpr int kUnits = 32 * WN / 8;
     const int mode = p.epilogue;  // BiasAct, MaskStore or GeluBwdStore
     const bf16_t* mask = static_cast<const bf16_t*>(p.mask);
     const bf16_t* res = static_cast<const bf16_t*>(p.residual);
@@ -207,7 +208,7 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
     for (int it = 0; it < kUnits / 64; ++it) {
       const int u = it * 64 + lane;
       const int row = u / (WN / 8), c = (u % (WN / 8)) * 8;
-      const int m = row_base + row, n = col_base + c;
+      const int m = piece_row + row, n = col_base + c;
       if (m >= p.M || n >= p.N) continue;
       float v[8], b[8], mk[8], r[8], pre[8];
       const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
@@ -240,6 +241,7 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
       }
     }
   }
+  }  // piece
 }
 
 template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
   constexpr int kLoadsPerTile = (BM + BN) / (8 * NW);  // direct-to-LDS instructions per wave per tile
   constexpr int kBatch = (TM + TN) <= 2 ? 4 : ((TM + TN) <= 4 ? 2 : 1);  // k-groups whose fragments are fetched together
-  static_assert((size_t)NW * WM * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
+  static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
@@ -336,7 +338,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   }
   if (want_row_sum && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = row_sum;
   wait_loads_and_barrier<0>();  // every wave is done with the tile ring
-  float* stage = reinterpret_cast<float*>(lds) + wave * (WM * (WN + 4));
+  float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (WN + 4));
   store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset(p.c_batch, z));
 }
 
@@ -358,10 +360,14 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// Tile choice.  A 256 x 256 tile reads half as many operand bytes per flop from L2 as a 128 x 128 one, which is
+// what large products need; it only pays once there are enough tiles for two rounds over the 256 CUs.  Small
+// products take 64 x 64 tiles and a deeper ring: they are bound by latency, not by bytes.
 template <Layout LA, Layout LB>
 hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
-  const long big_tiles = (long)((q.M + 127) / 128) * ((q.N + 127) / 128) * q.batch;
-  if (big_tiles >= 192) return launch_tile<128, 128, 3, 2, 2, LA, LB>(q, stream);
+  auto tiles = [&](int t) { return (long)((q.M + t - 1) / t) * ((q.N + t - 1) / t) * q.batch; };
+  if (tiles(256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB>(q, stream);
+  if (tiles(128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB>(q, stream);
   return launch_tile<64, 64, 4, 2, 2, LA, LB>(q, stream);
 }
 

@@ -45,7 +45,8 @@ def test_finite_differences_full_backward():
         assert np.abs(fd - grads[name]).max() / scale < 1e-6, name
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp_f32", "ragged_mlp_f32", "ragged_mlp_bf16", "tiny_encoder", "small_encoder_bf16"])
+@pytest.mark.parametrize("name", ["tiny_mlp_f32", "ragged_mlp_f32", "ragged_mlp_bf16", "tiny_encoder", "small_encoder_bf16",
+                                  "tiny_resnet_bottleneck", "small_resnet_basic_bf16"])
 @pytest.mark.parametrize("mode", ["exact", "bf16"])
 def test_suffix_properties(name, mode):
     """Depth k returns exactly the top-k units' parameters; their values do not

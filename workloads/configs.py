@@ -46,6 +46,18 @@ CONFIGS = {
                          vocab=11, loss_rows=3, depths=[0, 1, 2, 3, 4]),
     "small_encoder_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=2, hidden=64, heads=4,
                                ffn=136, vocab=203, loss_rows=17, depths=[0, 1, 2, 3, 4]),
+    "tiny_resnet_basic": dict(family="resnet_basic", dtype="bf16", batch=2, image=[6, 6, 3],
+                              stem=dict(kernel=3, stride=1, pad=1, pool=False, width=4),
+                              stage_blocks=[1, 1], stage_widths=[4, 6], classes=3, depths=[0, 1, 2, 3, 4]),
+    "tiny_resnet_bottleneck": dict(family="resnet_bottleneck", dtype="bf16", batch=2, image=[9, 9, 3],
+                                   stem=dict(kernel=7, stride=2, pad=3, pool=True, width=4),
+                                   stage_blocks=[2, 1], stage_widths=[8, 12], classes=3, depths=[0, 1, 2, 3, 4, 5]),
+    "small_resnet_basic_bf16": dict(family="resnet_basic", dtype="bf16", batch=3, image=[12, 12, 3],
+                                    stem=dict(kernel=3, stride=1, pad=1, pool=False, width=16),
+                                    stage_blocks=[1, 2], stage_widths=[16, 32], classes=7, depths=[0, 1, 2, 3, 4, 5]),
+    "small_resnet_bottleneck_bf16": dict(family="resnet_bottleneck", dtype="bf16", batch=2, image=[20, 20, 3],
+                                         stem=dict(kernel=7, stride=2, pad=3, pool=True, width=16),
+                                         stage_blocks=[2, 1], stage_widths=[32, 64], classes=11, depths=[0, 1, 2, 3, 4, 5]),
     "one_layer_bf16": dict(family="mlp", dtype="bf16", batch=16,
                            dims=[64, 10], depths=[0, 1]),
 }
@@ -70,3 +82,31 @@ def unit_count(cfg: dict) -> int:
 
 def depth_sweep(cfg: dict) -> list:
     return list(cfg["depths"])
+
+
+def resnet_layout(cfg: dict) -> dict:
+    """Shapes of a residual CNN: the stem, the list of blocks and the classifier input width.
+
+    Stride 2 sits on the first block of every stage but the first (in a bottleneck, on its 3x3 convolution);
+    a block whose input and output shapes differ gets a 1x1 projection shortcut with the same stride;
+    a bottleneck's inner width is a quarter of its output width.
+    """
+    st = cfg["stem"]
+    h = (cfg["image"][0] + 2 * st["pad"] - st["kernel"]) // st["stride"] + 1
+    w = (cfg["image"][1] + 2 * st["pad"] - st["kernel"]) // st["stride"] + 1
+    stem = dict(cin=cfg["image"][2], cout=st["width"], kernel=st["kernel"], stride=st["stride"], pad=st["pad"],
+                pool=bool(st["pool"]), conv_hw=(h, w))
+    if st["pool"]:
+        h, w = (h + 2 - 3) // 2 + 1, (w + 2 - 3) // 2 + 1
+    blocks, cin = [], st["width"]
+    bottleneck = cfg["family"] == "resnet_bottleneck"
+    for stage, (count, width) in enumerate(zip(cfg["stage_blocks"], cfg["stage_widths"])):
+        for j in range(count):
+            stride = 2 if (stage > 0 and j == 0) else 1
+            blk = dict(index=len(blocks), cin=cin, cout=width, mid=width // 4 if bottleneck else width, stride=stride,
+                       proj=(stride != 1 or cin != width), in_hw=(h, w))
+            h, w = (h - 1) // stride + 1, (w - 1) // stride + 1
+            blk["out_hw"] = (h, w)
+            blocks.append(blk)
+            cin = width
+    return dict(stem=stem, blocks=blocks, bottleneck=bottleneck, features=cin, final_hw=(h, w))

@@ -42,6 +42,36 @@ def tensor_specs(cfg: dict) -> list:
             specs.append((f"fc{i}.weight", (dims[i + 1], dims[i]), i, ("normal", (2.0 / fan_in) ** 0.5)))
             specs.append((f"fc{i}.bias", (dims[i + 1],), i, ("const", 0.0)))
         return specs
+    if fam in ("resnet_basic", "resnet_bottleneck"):
+        from .configs import resnet_layout
+        lay = resnet_layout(cfg)
+
+        def conv(name, unit, cout, k, cin):      # weights are [Cout, R, S, Cin]; He-normal with fan_in = Cin * R * S
+            specs.append((name + ".weight", (cout, k, k, cin), unit, ("normal", (2.0 / (cin * k * k)) ** 0.5)))
+
+        def affine(name, unit, c):               # the folded BatchNorm: trainable per-channel scale and shift
+            specs.append((name + ".scale", (c,), unit, ("const", 1.0)))
+            specs.append((name + ".shift", (c,), unit, ("const", 0.0)))
+
+        st = lay["stem"]
+        conv("stem.conv", 0, st["cout"], st["kernel"], st["cin"])
+        affine("stem.aff", 0, st["cout"])
+        for blk in lay["blocks"]:
+            u, pre = blk["index"] + 1, f"block{blk['index']}."
+            if lay["bottleneck"]:
+                chain = [(1, blk["cin"], blk["mid"]), (3, blk["mid"], blk["mid"]), (1, blk["mid"], blk["cout"])]
+            else:
+                chain = [(3, blk["cin"], blk["cout"]), (3, blk["cout"], blk["cout"])]
+            for j, (k, ci, co) in enumerate(chain, start=1):
+                conv(f"{pre}conv{j}", u, co, k, ci)
+                affine(f"{pre}aff{j}", u, co)
+            if blk["proj"]:
+                conv(pre + "proj", u, blk["cout"], 1, blk["cin"])
+                affine(pre + "projaff", u, blk["cout"])
+        u = len(lay["blocks"]) + 1
+        specs.append(("head.fc.weight", (cfg["classes"], lay["features"]), u, ("normal", (2.0 / lay["features"]) ** 0.5)))
+        specs.append(("head.fc.bias", (cfg["classes"],), u, ("const", 0.0)))
+        return specs
     if fam == "encoder":
         h, f, v, seq = cfg["hidden"], cfg["ffn"], cfg["vocab"], cfg["seq"]
         std = 0.02
@@ -89,6 +119,11 @@ def make_batch(cfg: dict, seed: int = 0) -> dict:
         b, d, c = cfg["batch"], cfg["dims"][0], cfg["dims"][-1]
         x = _store(_normal(seed, "batch/x", (b, d), 1.0), cfg["dtype"])
         labels = _stream(seed, "batch/labels").integers(0, c, size=(b,), dtype=np.int32)
+        return {"x": x, "labels": torch.from_numpy(labels)}
+    if fam in ("resnet_basic", "resnet_bottleneck"):
+        b, (h, w, c) = cfg["batch"], cfg["image"]
+        x = _store(_normal(seed, "batch/x", (b, h, w, c), 1.0), cfg["dtype"])        # NHWC
+        labels = _stream(seed, "batch/labels").integers(0, cfg["classes"], size=(b,), dtype=np.int32)
         return {"x": x, "labels": torch.from_numpy(labels)}
     if fam == "encoder":
         b, seq, v, rows = cfg["batch"], cfg["seq"], cfg["vocab"], cfg["loss_rows"]
