@@ -116,9 +116,7 @@ int spb_model_create(const spb_model_desc* desc, spb_model** out) {
     case SPB_FAMILY_MLP: impl = spb::make_mlp(*desc); break;
     case SPB_FAMILY_ENCODER: impl = spb::make_encoder(*desc); break;
     case SPB_FAMILY_RESNET_BASIC:
-    case SPB_FAMILY_RESNET_BOTTLENECK:
-      set_error("spb_model_create: family %d is not built into this library", desc->family);
-      return SPB_ERR_UNSUPPORTED;
+    case SPB_FAMILY_RESNET_BOTTLENECK: impl = spb::make_resnet(*desc); break;
     default:
       set_error("spb_model_create: unknown family %d", desc->family);
       return SPB_ERR_INVALID_ARG;

@@ -1,0 +1,254 @@
+// Memory-bound kernels of the residual-CNN units (activations NHWC bfloat16, channel counts multiples of 8):
+// the backward of "per-channel affine -> ReLU" with its per-channel reductions, the pools, channel padding of
+// the 3-channel input, and the fixed-order sum of split-k partial products.  Each moves every tensor through
+// HBM once, in 16-byte pieces along the channel index.
+#include "kernels.h"
+
+namespace spb {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack8(const u32x4& w, float (&f)[8]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
+}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
+}
+__device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
+  u32x4 o;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) o[d] = pack2(f[2 * d], f[2 * d + 1]);
+  return o;
+}
+__device__ __forceinline__ float bf(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ uint16_t to_bf16(float v) {
+  uint32_t u = __float_as_uint(v);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// Backward of z = scale * y + shift followed by an optional ReLU whose output is `act`:
+//   dz = dout * [act > 0]   (dz = dout without act);   dy = scale * dz;   dsum = dz (optional)
+//   partial[block][0][c] = sum over the block's rows of dz * y;   partial[block][1][c] = sum of dz
+// Thread t owns chunk t % chunks of rows (t / chunks), (t / chunks) + rows_per_pass, ...
+__global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __restrict__ dout, const uint16_t* __restrict__ act,
+                                                              const uint16_t* __restrict__ y, const uint16_t* __restrict__ scale,
+                                                              uint16_t* __restrict__ dy, uint16_t* __restrict__ dsum,
+                                                              float* __restrict__ partial, long long rows, int channels, int rows_per_block) {
+  extern __shared__ float sh[];  // [rows_per_pass][chunks][16]
+  const int chunks = channels >> 3;
+  const int rows_per_pass = 256 / chunks;
+  const int chunk = threadIdx.x % chunks, lane_row = threadIdx.x / chunks;
+  const bool active = lane_row < rows_per_pass;
+  float s1[8], s0[8], sc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { s1[e] = 0.f; s0[e] = 0.f; sc[e] = 0.f; }
+  if (active) unpack8(*reinterpret_cast<const u32x4*>(scale + chunk * 8), sc);
+  const long long first = (long long)blockIdx.x * rows_per_block;
+  const long long last = min(rows, first + rows_per_block);
+  if (active) {
+    for (long long r = first + lane_row; r < last; r += rows_per_pass) {
+      const size_t off = (size_t)r * channels + chunk * 8;
+      float d[8], yv[8], o[8];
+      unpack8(*reinterpret_cast<const u32x4*>(dout + off), d);
+      unpack8(*reinterpret_cast<const u32x4*>(y + off), yv);
+      if (act) {
+        float a[8];
+        unpack8(*reinterpret_cast<const u32x4*>(act + off), a);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) if (!(a[e] > 0.f)) d[e] = 0.f;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { s1[e] += d[e] * yv[e]; s0[e] += d[e]; o[e] = sc[e] * d[e]; }
+      *reinterpret_cast<u32x4*>(dy + off) = pack8(o);
+      if (dsum) *reinterpret_cast<u32x4*>(dsum + off) = pack8(d);
+    }
+    float* mine = sh + ((size_t)lane_row * chunks + chunk) * 16;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { mine[e] = s1[e]; mine[8 + e] = s0[e]; }
+  }
+  __syncthreads();
+  // column sums over the block's row lanes, in lane order
+  for (int col = threadIdx.x; col < 2 * channels; col += 256) {
+    const int which = col / channels, c = col % channels;
+    float acc = 0.f;
+    for (int l = 0; l < rows_per_pass; ++l) acc += sh[((size_t)l * chunks + (c >> 3)) * 16 + which * 8 + (c & 7)];
+    partial[(size_t)blockIdx.x * 2 * channels + col] = acc;
+  }
+}
+
+// out[c] sums: same layout as the LayerNorm partials ([blocks][2][width]); blocks added in index order.
+__global__ __launch_bounds__(256) void reduce_pairs_kernel(const float* __restrict__ partial, int n_blocks, int width,
+                                                           float* __restrict__ out_a, float* __restrict__ out_b) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= 2 * width) return;
+  float s = 0.f;
+  for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * 2 * width + col];
+  if (col < width) out_a[col] = s;
+  else out_b[col - width] = s;
+}
+
+// out[j] = sum over slices of partial[slice][map(j)], slices added in index order; map drops padded input channels.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices, long long slice_stride,
+                                                            float* __restrict__ out, long long numel, int cin, int cin_padded) {
+  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (j >= numel) return;
+  const long long src = cin == cin_padded ? j : (j / cin) * cin_padded + (j % cin);
+  float s = 0.f;
+  for (int z = 0; z < slices; ++z) s += partial[(size_t)z * slice_stride + src];
+  out[j] = s;
+}
+
+// 3x3 window, stride 2, padding 1 (acting as -inf); the first maximum in row-major window order wins.
+// which[n, oh, ow, c] (optional) = index 0..8 of the winning window position.
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ out, uint8_t* __restrict__ which,
+                                                          int n, int h, int w, int c, int oh, int ow) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)n * oh * ow * c) return;
+  const int ch = idx % c;
+  long long t = idx / c;
+  const int j = t % ow; t /= ow;
+  const int i = t % oh;
+  const int b = t / oh;
+  float best = -INFINITY;
+  int arg = 0;
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      const int hi = 2 * i + r - 1, wi = 2 * j + s - 1;
+      if ((unsigned)hi < (unsigned)h && (unsigned)wi < (unsigned)w) {
+        const float v = bf(x[((size_t)(b * h + hi) * w + wi) * c + ch]);
+        if (v > best) { best = v; arg = r * 3 + s; }
+      }
+    }
+  out[idx] = to_bf16(best);
+  if (which) which[idx] = (uint8_t)arg;
+}
+
+// da[n, h, w, c] = sum of dout over the (at most 4) windows whose maximum sat at (h, w).
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const uint16_t* __restrict__ dout, const uint8_t* __restrict__ which,
+                                                          uint16_t* __restrict__ da, int n, int h, int w, int c, int oh, int ow) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)n * h * w * c) return;
+  const int ch = idx % c;
+  long long t = idx / c;
+  const int wi = t % w; t /= w;
+  const int hi = t % h;
+  const int b = t / h;
+  float acc = 0.f;
+  for (int i = (hi + 1) / 2 - (hi & 1); i <= (hi + 1) / 2; ++i) {     // windows with 2i-1 <= hi <= 2i+1: one for even hi, two for odd
+    if (i < 0 || i >= oh) continue;
+    for (int j = (wi + 1) / 2 - (wi & 1); j <= (wi + 1) / 2; ++j) {
+      if (j < 0 || j >= ow) continue;
+      const size_t o = ((size_t)(b * oh + i) * ow + j) * c + ch;
+      if (which[o] == (hi - 2 * i + 1) * 3 + (wi - 2 * j + 1)) acc += bf(dout[o]);
+    }
+  }
+  da[idx] = to_bf16(acc);
+}
+
+// pooled[n, c] = mean over the hw pixels of x[n, :, c]
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ pooled, int n, int hw, int c) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n * c) return;
+  const int b = idx / c, ch = idx % c;
+  float acc = 0.f;
+  for (int p = 0; p < hw; ++p) acc += bf(x[((size_t)b * hw + p) * c + ch]);
+  pooled[idx] = to_bf16(acc / (float)hw);
+}
+
+// dx[n, p, c] = dpooled[n, c] / hw
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const uint16_t* __restrict__ dpooled, uint16_t* __restrict__ dx, int n, int hw, int c) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)n * hw * c) return;
+  const int ch = idx % c;
+  const int b = idx / ((long long)hw * c);
+  dx[idx] = to_bf16(bf(dpooled[b * c + ch]) / (float)hw);
+}
+
+// out[row, 0..c_out) = in[row, 0..c_in) followed by zeros
+__global__ __launch_bounds__(256) void pad_channels_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out, long long rows, int c_in, int c_out) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * c_out) return;
+  const int ch = idx % c_out;
+  out[idx] = ch < c_in ? in[(idx / c_out) * c_in + ch] : (uint16_t)0;
+}
+
+unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
+
+}  // namespace
+
+// rows handled by one workgroup of the affine backward kernel, and the size of its partial buffer
+static int affine_rows_per_block(long long rows, int channels) {
+  const int per_pass = 256 / (channels >> 3);
+  long long want = (rows + 1023) / 1024;                      // about a thousand workgroups
+  want = (want + per_pass - 1) / per_pass * per_pass;
+  return (int)(want < per_pass ? per_pass : want);
+}
+size_t affine_partial_floats(long long rows, int channels) {
+  const int rpb = affine_rows_per_block(rows, channels);
+  return (size_t)((rows + rpb - 1) / rpb) * 2 * channels;
+}
+
+hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void* y, const void* scale, void* dy, void* dsum,
+                                  float* partial, float* dscale, float* dshift, long long rows, int channels, hipStream_t s) {
+  if (!dout || !y || !scale || !dy || !partial || !dscale || !dshift || rows <= 0 || channels <= 0 || channels % 8 || channels > 2048)
+    return hipErrorInvalidValue;
+  const int rpb = affine_rows_per_block(rows, channels);
+  const int blocks = (int)((rows + rpb - 1) / rpb);
+  const int per_pass = 256 / (channels >> 3);
+  const size_t lds = (size_t)per_pass * (channels >> 3) * 16 * sizeof(float);
+  hipLaunchKernelGGL(affine_relu_bwd_kernel, dim3(blocks), dim3(256), lds, s, (const uint16_t*)dout, (const uint16_t*)act, (const uint16_t*)y,
+                     (const uint16_t*)scale, (uint16_t*)dy, (uint16_t*)dsum, partial, rows, channels, rpb);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(reduce_pairs_kernel, dim3((2 * channels + 255) / 256), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,
+                                hipStream_t s) {
+  if (!partial || !out || slices < 1 || numel <= 0 || cin <= 0 || cin_padded < cin) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(numel)), dim3(256), 0, s, partial, slices, slice_stride, out, numel, cin, cin_padded);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_fwd(const void* x, void* out, uint8_t* which, int n, int h, int w, int c, hipStream_t s) {
+  if (!x || !out || n <= 0 || h <= 0 || w <= 0 || c <= 0) return hipErrorInvalidValue;
+  const int oh = (h - 1) / 2 + 1, ow = (w - 1) / 2 + 1;
+  hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for((long long)n * oh * ow * c)), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)out, which, n, h, w, c, oh, ow);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(const void* dout, const uint8_t* which, void* da, int n, int h, int w, int c, hipStream_t s) {
+  if (!dout || !which || !da || n <= 0 || h <= 0 || w <= 0 || c <= 0) return hipErrorInvalidValue;
+  const int oh = (h - 1) / 2 + 1, ow = (w - 1) / 2 + 1;
+  hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for((long long)n * h * w * c)), dim3(256), 0, s, (const uint16_t*)dout, which, (uint16_t*)da, n, h, w, c, oh, ow);
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_fwd(const void* x, void* pooled, int n, int hw, int c, hipStream_t s) {
+  if (!x || !pooled || n <= 0 || hw <= 0 || c <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(avgpool_fwd_kernel, dim3(blocks_for((long long)n * c)), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)pooled, n, hw, c);
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_bwd(const void* dpooled, void* dx, int n, int hw, int c, hipStream_t s) {
+  if (!dpooled || !dx || n <= 0 || hw <= 0 || c <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(avgpool_bwd_kernel, dim3(blocks_for((long long)n * hw * c)), dim3(256), 0, s, (const uint16_t*)dpooled, (uint16_t*)dx, n, hw, c);
+  return hipGetLastError();
+}
+
+hipError_t launch_pad_channels(const void* in, void* out, long long rows, int c_in, int c_out, hipStream_t s) {
+  if (!in || !out || rows <= 0 || c_in <= 0 || c_out < c_in) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks_for(rows * c_out)), dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, rows, c_in, c_out);
+  return hipGetLastError();
+}
+
+}  // namespace spb

@@ -283,7 +283,12 @@ double gemm_flops(const GemmProblem& p) { return 2.0 * p.M * p.N * p.K * p.batch
 double gemm_bytes(const GemmProblem& p) {
   const double es = (double)dtype_size(p.dtype);
   const double out = p.epilogue == Epilogue::StoreF32 ? 4.0 : es;
-  double b = es * ((double)p.M * p.K + (double)p.N * p.K) + out * (double)p.M * p.N;
+  // an implicit-GEMM operand is the tensor it is gathered from, read once, not its unrolled matrix
+  const double tensor = (double)p.conv.n * p.conv.sh * p.conv.sw * p.conv.sc;
+  const double a = p.a_gather == Gather::ConvRows ? tensor : (double)p.M * p.K;
+  const double bm = p.b_gather == Gather::ConvPatchT ? tensor
+                  : p.b_gather == Gather::ConvWeightT ? (double)p.conv.w_cout * p.conv.r * p.conv.s * p.conv.w_cin : (double)p.N * p.K;
+  double b = es * (a + bm) + out * (double)p.M * p.N * p.k_splits;
   if (p.mask) b += es * (double)p.M * p.N;
   if (p.residual) b += es * (double)p.M * p.N;
   if (p.aux_out) b += es * (double)p.M * p.N;

@@ -38,10 +38,12 @@ __device__ __forceinline__ void store_elem(bf16_t* p, float v) {
 struct GemmParams {
   const void* A; const void* B; void* C;
   const void* bias; const void* mask; float* a_row_sum;
-  const void* residual; void* aux_out;
+  const void* residual; void* aux_out; const void* col_scale;
   int M, N, K, lda, ldb, ldc, ldmask, ldres, ldaux;
-  int epilogue, act;
+  int epilogue, act, aux_raw;
   float alpha;
+  int k_tiles_per_split;  // 0: blockIdx.y is a batch entry; > 0: blockIdx.y is a slice of the k range
+  ConvGeom conv;
   int tiles_m, tiles_n;
   BatchStride a_batch, b_batch, c_batch;
 };
@@ -94,7 +96,9 @@ inline GemmParams make_params(const GemmProblem& q, int bm, int bn) {
   p.M = q.M; p.N = q.N; p.K = q.K; p.lda = q.lda; p.ldb = q.ldb; p.ldc = q.ldc; p.ldmask = q.ldmask;
   p.residual = q.residual; p.aux_out = q.aux_out; p.ldres = q.ldres; p.ldaux = q.ldaux;
   p.epilogue = (int)q.epilogue; p.act = q.relu ? (int)Act::Relu : (int)q.act;
-  p.alpha = q.alpha;
+  p.alpha = q.alpha; p.col_scale = q.col_scale; p.aux_raw = q.aux_raw;
+  p.conv = q.conv;
+  p.k_tiles_per_split = 0;
   p.a_batch = q.a_batch; p.b_batch = q.b_batch; p.c_batch = q.c_batch;
   p.tiles_m = (q.M + bm - 1) / bm;
   p.tiles_n = (q.N + bn - 1) / bn;

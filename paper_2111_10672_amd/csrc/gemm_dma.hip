@@ -51,21 +51,30 @@ __device__ __forceinline__ int krow_rot(int k) {
 }
 
 // Where one lane's 16-byte chunks of an operand tile come from.  Everything that does not change from
-// tile to tile is worked out once: per tile a lane adds the tile's byte offset and checks the k bound.
+// tile to tile is worked out once; tiles are issued in increasing order, so what does change (the tap and
+// channel a chunk's k falls on, the pixel a k-row stands for) is stepped, never divided out again.
 // Every wave issues exactly kInstr direct-to-LDS instructions per tile, whatever its lanes' predicates:
-// a lane outside the matrix fetches a chunk of zeros instead, so the vmcnt arithmetic of the tile loop
-// holds and rows or k beyond the matrix multiply as zero.
-template <int ROWS, Layout L, int NW>
+// a lane outside the matrix (or in a convolution's zero padding) fetches a chunk of zeros instead, so the
+// vmcnt arithmetic of the tile loop holds and rows or k beyond the matrix multiply as zero.
+template <int ROWS, Layout L, Gather G, int NW>
 struct TileSource {
   static constexpr int kInstr = ROWS / (8 * NW);
   static_assert(ROWS % (8 * NW) == 0 && kInstr >= 1, "tile rows must fill whole wave instructions");
-  const char* ptr[kInstr];  // this lane's chunk in tile 0 (not dereferenced unless in range)
+  static_assert(G == Gather::None || (G == Gather::ConvRows) == (L == Layout::RowK), "gather kind fixes the LDS layout");
+  const char* ptr[kInstr];  // Plain: this lane's chunk in tile 0.  Gathers: the tensor's base.
   int k_in_tile[kInstr];    // k of the chunk's first element relative to the tile start
   bool in_rows[kInstr];
-  size_t tile_step;         // bytes from one tile to the next
+  int row_idx[kInstr];      // first row (of the operand) this lane's chunk covers
+  size_t tile_step;         // Plain: bytes from one tile to the next
+  // gather state, per instruction
+  int tap[kInstr], chan[kInstr];           // ConvRows, ConvWeightT: where this lane's k of the next tile falls; ConvPatchT: fixed (tap, ci) of its rows
+  int g0[kInstr], g1[kInstr], g2[kInstr];  // ConvRows: pixel base, row term, column term.  ConvPatchT: image, pixel in image of the next tile's k-row.
+  int step_q, step_r;                      // one tile further: quotient and remainder of 64 by the modulus being stepped
 
-  __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int wave, int lane) {
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int wave, int lane, int t0, const ConvGeom& cg) {
     tile_step = L == Layout::RowK ? (size_t)kTileK * 2 : (size_t)kTileK * ld * 2;
+    const int modulus = G == Gather::ConvRows ? cg.sc : G == Gather::ConvWeightT ? cg.w_cout : cg.rh * cg.rw;
+    if constexpr (G != Gather::None) { step_q = kTileK / modulus; step_r = kTileK % modulus; }
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) {
       const int slot = (i * NW + wave) * 64 + lane;
@@ -74,26 +83,82 @@ struct TileSource {
         const int row = slot >> 3, pc = slot & 7;
         gr = row0 + row;
         k = ((pc ^ row ^ (row >> 3)) & 7) << 3;
-        ptr[i] = reinterpret_cast<const char*>(base + (size_t)gr * ld + k);
       } else {
         constexpr int kRowChunks = ROWS / 8;
         k = slot / kRowChunks;
         const int pc = slot % kRowChunks;
         gr = row0 + (((pc - krow_rot<ROWS>(k)) & (kRowChunks - 1)) << 3);
-        ptr[i] = reinterpret_cast<const char*>(base + (size_t)k * ld + gr);
       }
       k_in_tile[i] = k;
       in_rows[i] = gr < nrows;
+      row_idx[i] = gr;
+      if constexpr (G == Gather::None) {
+        ptr[i] = reinterpret_cast<const char*>(L == Layout::RowK ? base + (size_t)gr * ld + k : base + (size_t)k * ld + gr) + (size_t)t0 * tile_step;
+      } else {
+        ptr[i] = reinterpret_cast<const char*>(base);
+        const int k_abs = t0 * kTileK + k;
+        if constexpr (G == Gather::ConvRows) {        // row gr = pixel (n, a, b); k = (tap, channel)
+          const int per_image = cg.rh * cg.rw;
+          const int n = gr / per_image, rem = gr - n * per_image;
+          const int a = rem / cg.rw, b = rem - a * cg.rw;
+          g0[i] = n * cg.sh * cg.sw;
+          g1[i] = cg.transposed ? a + cg.pad : a * cg.stride - cg.pad;
+          g2[i] = cg.transposed ? b + cg.pad : b * cg.stride - cg.pad;
+          tap[i] = k_abs / cg.sc; chan[i] = k_abs - tap[i] * cg.sc;
+        } else if constexpr (G == Gather::ConvWeightT) {  // row gr = ci; k = (tap, co)
+          tap[i] = k_abs / cg.w_cout; chan[i] = k_abs - tap[i] * cg.w_cout;
+        } else {                                          // row gr = (tap, ci); k = output pixel m
+          tap[i] = gr / cg.sc; chan[i] = gr - tap[i] * cg.sc;
+          const int per_image = cg.rh * cg.rw;
+          g0[i] = k_abs / per_image; g1[i] = k_abs - g0[i] * per_image; g2[i] = 0;
+        }
+      }
     }
   }
-  __device__ __forceinline__ void issue(int t, int K, char* tile, int wave) const {
+
+  // Issue tile t (tiles must be issued in increasing order, one after the other).
+  __device__ __forceinline__ void issue(int t, int K, char* tile, int wave, int ld, const ConvGeom& cg) {
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) {
       const char* src = reinterpret_cast<const char*>(kZeroChunk);
-      if (in_rows[i] && t * kTileK + k_in_tile[i] < K) src = ptr[i] + (size_t)t * tile_step;
+      if constexpr (G == Gather::None) {
+        if (in_rows[i] && t * kTileK + k_in_tile[i] < K) src = ptr[i];
+        ptr[i] += tile_step;
+      } else if constexpr (G == Gather::ConvRows) {
+        const int taps = cg.r * cg.s;
+        const int r = (tap[i] * (65536 / cg.s + 1)) >> 16, c = tap[i] - r * cg.s;   // tap = r * S + c, exact for tap < 256
+        int hi, wi;
+        bool ok = in_rows[i] && tap[i] < taps;
+        if (!cg.transposed) {
+          hi = g1[i] + r; wi = g2[i] + c;
+        } else {
+          const int th = g1[i] - r, tw = g2[i] - c, m = cg.stride - 1;   // stride is 1 or 2
+          ok = ok && th >= 0 && tw >= 0 && ((th | tw) & m) == 0;
+          hi = th >> m; wi = tw >> m;
+        }
+        ok = ok && (unsigned)hi < (unsigned)cg.sh && (unsigned)wi < (unsigned)cg.sw;
+        if (ok) src = ptr[i] + ((size_t)(g0[i] + hi * cg.sw + wi) * cg.sc + chan[i]) * 2;
+        chan[i] += step_r; tap[i] += step_q;
+        if (chan[i] >= cg.sc) { chan[i] -= cg.sc; ++tap[i]; }
+      } else if constexpr (G == Gather::ConvWeightT) {
+        const int taps = cg.r * cg.s;
+        if (in_rows[i] && tap[i] < taps) src = ptr[i] + (((size_t)chan[i] * taps + tap[i]) * cg.w_cin + row_idx[i]) * 2;
+        chan[i] += step_r; tap[i] += step_q;
+        if (chan[i] >= cg.w_cout) { chan[i] -= cg.w_cout; ++tap[i]; }
+      } else {
+        const int r = (tap[i] * (65536 / cg.s + 1)) >> 16, c = tap[i] - r * cg.s;
+        const int oh = __float2int_rz(((float)g1[i] + 0.5f) * (1.0f / (float)cg.rw)), ow = g1[i] - oh * cg.rw;
+        const int hi = oh * cg.stride + r - cg.pad, wi = ow * cg.stride + c - cg.pad;
+        if (in_rows[i] && g0[i] < cg.n && (unsigned)hi < (unsigned)cg.sh && (unsigned)wi < (unsigned)cg.sw)
+          src = ptr[i] + ((size_t)((g0[i] * cg.sh + hi) * cg.sw + wi) * cg.sc + chan[i]) * 2;
+        const int per_image = cg.rh * cg.rw;
+        g1[i] += step_r; g0[i] += step_q;
+        if (g1[i] >= per_image) { g1[i] -= per_image; ++g0[i]; }
+      }
       __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, 0, 0);
     }
   }
+
 };
 
 // Fetch the MFMA operand of one 32-row fragment for k-group kg (16 values of k): 8 bfloat16 per lane.
@@ -195,14 +260,19 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
       return o;
     };
     // one element of the epilogue, shared by the 16-byte path and the ragged tail
+    const bf16_t* cscale = static_cast<const bf16_t*>(p.col_scale);
+    // (in BiasAct mode mk carries the column scale, 1 if there is none)
     auto finish = [&](float v, float b, float mk, float r, float& pre) {
       if (mode == (int)Epilogue::MaskStore) return mk > 0.f ? v : 0.f;
       if (mode == (int)Epilogue::GeluBwdStore) return v * gelu_grad_f(mk);
-      v = v * p.alpha + b;
+      v *= p.alpha;
       pre = v;
+      v = v * mk + b;
+      if (!p.aux_raw) pre = v;
+      v += r;                                   // a residual joins before the activation (residual blocks)
       if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
       else if (p.act == (int)Act::Gelu) v = gelu_f(v);
-      return v + r;
+      return v;
     };
 #pragma unroll
     for (int it = 0; it < kUnits / 64; ++it) {
@@ -222,6 +292,11 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
         if (mode != (int)Epilogue::BiasAct) {
           unpack(*reinterpret_cast<const u32x4*>(mask + (size_t)m * p.ldmask + n), mk);
         } else {
+          if (cscale) unpack(*reinterpret_cast<const u32x4*>(cscale + n), mk);
+          else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mk[e] = 1.f;
+          }
           if (bias) unpack(*reinterpret_cast<const u32x4*>(bias + n), b);
           if (res) unpack(*reinterpret_cast<const u32x4*>(res + (size_t)m * p.ldres + n), r);
         }
@@ -233,7 +308,7 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
         for (int e = 0; e < 8 && n + e < p.N; ++e) {
           float be = 0.f, me = 0.f, re = 0.f, pe = 0.f;
           if (mode != (int)Epilogue::BiasAct) me = to_float(mask[(size_t)m * p.ldmask + n + e]);
-          else { if (bias) be = to_float(bias[n + e]); if (res) re = to_float(res[(size_t)m * p.ldres + n + e]); }
+          else { me = cscale ? to_float(cscale[n + e]) : 1.f; if (bias) be = to_float(bias[n + e]); if (res) re = to_float(res[(size_t)m * p.ldres + n + e]); }
           const float x = finish(v[e], be, me, re, pe);
           if (aux && mode == (int)Epilogue::BiasAct) store_elem(aux + (size_t)m * p.ldaux + n + e, pe);
           store_elem(dst + e, x);
@@ -244,7 +319,7 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
   }  // piece
 }
 
-template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB, Gather GA, Gather GB>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(GemmParams p) {
   constexpr int NW = WAVES_M * WAVES_N;
   static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
@@ -265,20 +340,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave % WAVES_M, wn = wave / WAVES_M;
 
-  TileSource<BM, LA, NW> src_a;
-  TileSource<BN, LB, NW> src_b;
-  const int z = blockIdx.y;  // batch entry
-  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset(p.a_batch, z), p.lda, m0, p.M, wave, lane);
-  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset(p.b_batch, z), p.ldb, n0, p.N, wave, lane);
-  const int n_steps = (p.K + kTileK - 1) / kTileK;
+  TileSource<BM, LA, GA, NW> src_a;
+  TileSource<BN, LB, GB, NW> src_b;
+  const int z = blockIdx.y;  // batch entry, or slice of the k range
+  int t_first = 0, n_steps = (p.K + kTileK - 1) / kTileK;
+  if (p.k_tiles_per_split > 0) {
+    t_first = z * p.k_tiles_per_split;
+    n_steps = min(n_steps, t_first + p.k_tiles_per_split);
+  }
+  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset(p.a_batch, z), p.lda, m0, p.M, wave, lane, t_first, p.conv);
+  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset(p.b_batch, z), p.ldb, n0, p.N, wave, lane, t_first, p.conv);
   auto issue = [&](int t) {
-    char* stage = lds + (t % STAGES) * kStageBytes;
-    src_a.issue(t, p.K, stage, wave);
-    src_b.issue(t, p.K, stage + BM * kRowBytes, wave);
+    char* stage = lds + ((t - t_first) % STAGES) * kStageBytes;
+    src_a.issue(t, p.K, stage, wave, p.lda, p.conv);
+    src_b.issue(t, p.K, stage + BM * kRowBytes, wave, p.ldb, p.conv);
   };
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (s < n_steps) issue(s);
+    if (t_first + s < n_steps) issue(t_first + s);
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -291,12 +370,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   const bool want_row_sum = LA == Layout::KRow && p.a_row_sum != nullptr && tile_n == 0;
   float row_sum = 0.f;
 
-  for (int t = 0; t < n_steps; ++t) {
+  for (int t = t_first; t < n_steps; ++t) {
     // Tiles t+1 .. t+STAGES-2 may stay in flight if they were all issued; near the end wait for everything.
     if (t + STAGES - 2 < n_steps) wait_loads_and_barrier<(STAGES - 2) * kLoadsPerTile>();
     else wait_loads_and_barrier<0>();
     if (t + STAGES - 1 < n_steps) issue(t + STAGES - 1);
-    const char* as = lds + (t % STAGES) * kStageBytes;
+    const char* as = lds + ((t - t_first) % STAGES) * kStageBytes;
     const char* bs = as + BM * kRowBytes;
 #pragma unroll
     for (int kb = 0; kb < 4; kb += kBatch) {
@@ -342,12 +421,19 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset(p.c_batch, z));
 }
 
-template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB>
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB, Gather GA, Gather GB>
 hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
   GemmParams p = make_params(q, BM, BN);
+  int grid_y = q.batch;
+  if (q.k_splits > 1) {
+    const int tiles = (q.K + kTileK - 1) / kTileK;
+    p.k_tiles_per_split = (tiles + q.k_splits - 1) / q.k_splits;
+    p.c_batch.outer = (long long)q.M * q.ldc; p.c_batch.inner = 0; p.c_batch.inner_count = 1;
+    grid_y = q.k_splits;
+  }
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kRowBytes;
   static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
-  auto kernel = gemm_bf16_dma_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, LA, LB>;
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, LA, LB, GA, GB>;
   if (lds_bytes > 64 * 1024) {
     static bool raised = false;  // per instantiation
     if (!raised) {
@@ -356,19 +442,19 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
       raised = true;
     }
   }
-  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, q.batch), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
 // Tile choice.  A 256 x 256 tile reads half as many operand bytes per flop from L2 as a 128 x 128 one, which is
 // what large products need; it only pays once there are enough tiles for two rounds over the 256 CUs.  Small
 // products take 64 x 64 tiles and a deeper ring: they are bound by latency, not by bytes.
-template <Layout LA, Layout LB>
+template <Layout LA, Layout LB, Gather GA = Gather::None, Gather GB = Gather::None>
 hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
-  auto tiles = [&](int t) { return (long)((q.M + t - 1) / t) * ((q.N + t - 1) / t) * q.batch; };
-  if (tiles(256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB>(q, stream);
-  if (tiles(128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB>(q, stream);
-  return launch_tile<64, 64, 4, 2, 2, LA, LB>(q, stream);
+  auto tiles = [&](int t) { return (long)((q.M + t - 1) / t) * ((q.N + t - 1) / t) * q.batch * q.k_splits; };
+  if (tiles(256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
+  if (tiles(128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
+  return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
 }
 
 }  // namespace
@@ -388,6 +474,13 @@ bool gemm_dma_accepts(const GemmProblem& p) {
   if (reads_mask && (!p.mask || p.ldmask % 8 || !a16(p.mask))) return false;
   if (p.residual && (p.ldres % 8 || !a16(p.residual))) return false;
   if (p.aux_out && (p.ldaux % 8 || !a16(p.aux_out))) return false;
+  if (p.col_scale && !a16(p.col_scale)) return false;
+  if (p.k_splits < 1 || p.k_splits > 65535 || (p.k_splits > 1 && (p.epilogue != Epilogue::StoreF32 || p.batch != 1 || p.bias || p.a_row_sum))) return false;
+  if (p.a_gather != Gather::None || p.b_gather != Gather::None) {
+    const ConvGeom& c = p.conv;
+    if (c.sc % 8 || c.r * c.s > 255 || (c.stride != 1 && c.stride != 2) || c.rh <= 0 || c.rw <= 0 || c.rh * c.rw > 65535) return false;
+    if (p.b_gather == Gather::ConvWeightT && (c.w_cin % 8 || c.w_cout % 8)) return false;
+  }
   if (p.batch < 1 || p.batch > 65535 || (p.batch > 1 && p.a_row_sum)) return false;
   // batch offsets must keep every operand 16-byte aligned
   for (const BatchStride* b : {&p.a_batch, &p.b_batch, &p.c_batch})
@@ -396,6 +489,13 @@ bool gemm_dma_accepts(const GemmProblem& p) {
 }
 
 hipError_t launch_gemm_dma(const GemmProblem& p, hipStream_t stream) {
+  if (p.a_gather == Gather::ConvRows && p.b_gather == Gather::None && p.b_layout == Layout::RowK)
+    return launch_layouts<Layout::RowK, Layout::RowK, Gather::ConvRows, Gather::None>(p, stream);
+  if (p.a_gather == Gather::ConvRows && p.b_gather == Gather::ConvWeightT)
+    return launch_layouts<Layout::RowK, Layout::KRow, Gather::ConvRows, Gather::ConvWeightT>(p, stream);
+  if (p.a_gather == Gather::None && p.a_layout == Layout::KRow && p.b_gather == Gather::ConvPatchT)
+    return launch_layouts<Layout::KRow, Layout::KRow, Gather::None, Gather::ConvPatchT>(p, stream);
+  if (p.a_gather != Gather::None || p.b_gather != Gather::None) return hipErrorInvalidValue;
   if (p.a_layout == Layout::RowK && p.b_layout == Layout::RowK) return launch_layouts<Layout::RowK, Layout::RowK>(p, stream);
   if (p.a_layout == Layout::RowK && p.b_layout == Layout::KRow) return launch_layouts<Layout::RowK, Layout::KRow>(p, stream);
   if (p.a_layout == Layout::KRow && p.b_layout == Layout::KRow) return launch_layouts<Layout::KRow, Layout::KRow>(p, stream);

@@ -25,6 +25,22 @@ enum class Epilogue : int {
 
 enum class Act : int { None = 0, Relu = 1, Gelu = 2 };
 
+// An operand that is not a stored matrix but a view of an NHWC tensor (implicit GEMM of a convolution).
+enum class Gather : int {
+  None = 0,
+  ConvRows = 1,     // A, RowK: row m = pixel (n, a, b) of a [N, RH, RW] grid; k = (tap, channel) of the gathered tensor
+  ConvWeightT = 2,  // B, KRow: weights [Cout][R*S][Cin] read as B(ci, (tap, co))            (input-gradient product)
+  ConvPatchT = 3,   // B, KRow: B((tap, ci), m) = x[pixel(m) shifted by tap][ci]             (weight-gradient product)
+};
+
+struct ConvGeom {
+  int n = 0, sh = 0, sw = 0, sc = 0;  // the gathered tensor: [n, sh, sw, sc], NHWC
+  int rh = 0, rw = 0;                 // spatial size of the grid the implicit matrix's pixel index runs over
+  int r = 1, s = 1, stride = 1, pad = 0;
+  int transposed = 0;                 // 0: source = grid * stride + tap - pad; 1: source = (grid + pad - tap) / stride if divisible
+  int w_cin = 0, w_cout = 0;          // ConvWeightT: the weight tensor is [w_cout][r * s][w_cin]
+};
+
 // Element offset of batch entry z of an operand: (z / inner_count) * outer + (z % inner_count) * inner.
 struct BatchStride {
   long long outer = 0, inner = 0;
@@ -45,8 +61,15 @@ struct GemmProblem {
   float alpha = 1.f;
   const void* residual = nullptr; int ldres = 0;   // [M, N], dtype, added after the activation (BiasAct)
   void* aux_out = nullptr; int ldaux = 0;          // [M, N], dtype, receives the pre-activation (BiasAct)
+  const void* col_scale = nullptr;                 // [N], dtype: v = alpha * acc * col_scale[n] + bias[n]   (BiasAct)
+  int aux_raw = 0;                                 // aux_out receives alpha * acc instead of the pre-activation
   int batch = 1;                  // independent products launched together (attention heads)
   BatchStride a_batch, b_batch, c_batch;
+  Gather a_gather = Gather::None, b_gather = Gather::None;
+  ConvGeom conv;
+  // > 1: the k range is cut into k_splits slices; slice z writes its float32 partial product to C + z * M * ldc
+  // (StoreF32 only); the caller adds the slices up.
+  int k_splits = 1;
   const void* mask = nullptr; int ldmask = 0;   // [M, N], dtype
   // The buffer's owner keeps zeros between the end of each row's data and the next multiple of 8 elements
   // along the contiguous index (lets a kernel fetch whole 16-byte chunks).
@@ -72,6 +95,26 @@ hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labe
                                hipStream_t stream);
 
 hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
+
+// ---- memory-bound kernels of the residual-CNN units (NHWC bfloat16, channels % 8 == 0, <= 2048) ----
+// Backward of "per-channel affine, then optional ReLU whose output is act": dz = dout * [act > 0] (dz = dout if act is
+// null); dy = scale * dz; dsum = dz (optional); dscale[c] = sum dz * y; dshift[c] = sum dz (float32, overwritten).
+// partial: scratch of affine_partial_floats(rows, channels) floats.
+size_t affine_partial_floats(long long rows, int channels);
+hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void* y, const void* scale, void* dy, void* dsum,
+                                  float* partial, float* dscale, float* dshift, long long rows, int channels, hipStream_t s);
+// out[j] = sum over slices of partial[slice * slice_stride + map(j)], j < numel; map(j) = j, or with cin < cin_padded
+// (j / cin) * cin_padded + j % cin (drops the zero channels a 3-channel input was padded with).
+hipError_t launch_splitk_reduce(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,
+                                hipStream_t s);
+// 3x3 / stride 2 / padding 1 max-pool of x [n, h, w, c]; which (optional, [n, oh, ow, c]) records the winning window position.
+hipError_t launch_maxpool_fwd(const void* x, void* out, uint8_t* which, int n, int h, int w, int c, hipStream_t s);
+hipError_t launch_maxpool_bwd(const void* dout, const uint8_t* which, void* da, int n, int h, int w, int c, hipStream_t s);
+// global average pool of x [n, hw, c] -> pooled [n, c], and its backward (broadcast / hw)
+hipError_t launch_avgpool_fwd(const void* x, void* pooled, int n, int hw, int c, hipStream_t s);
+hipError_t launch_avgpool_bwd(const void* dpooled, void* dx, int n, int hw, int c, hipStream_t s);
+// out[row, :] = in[row, :c_in] followed by zeros up to c_out
+hipError_t launch_pad_channels(const void* in, void* out, long long rows, int c_in, int c_out, hipStream_t s);
 
 // ---- row-wise kernels of the encoder units (bfloat16 rows of `width` elements, width % 8 == 0, <= 2048) ----
 // y[r] = LayerNorm(x[rows ? rows[r] : r]) for r < n_rows; stats[r] = (mean, 1 / sqrt(var + 1e-5)).

@@ -70,6 +70,7 @@ class Model {
 
 std::unique_ptr<Model> make_mlp(const spb_model_desc& d);
 std::unique_ptr<Model> make_encoder(const spb_model_desc& d);
+std::unique_ptr<Model> make_resnet(const spb_model_desc& d);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -1,0 +1,443 @@
+// Residual-CNN families: units = stem | residual blocks (basic or bottleneck) | pooled classifier.
+// Forward pass, stash plan and truncated backward pass (Sec. 1-2 of the paper; ResNets are the paper's own
+// workloads, Tables 1-2).
+//
+// Every convolution is an implicit GEMM on the MFMA kernel of gemm_dma.hip, activations NHWC, weights
+// [Cout, R, S, Cin]:
+//   forward          out[pixel, co]  = sum_{tap, ci} x[pixel + tap][ci] * w[co][tap][ci]       rows gathered from x
+//   input gradient   dx[pixel, ci]   = sum_{tap, co} dy[(pixel - tap) / stride][co] * w[co][tap][ci]
+//   weight gradient  dw[co][tap][ci] = sum_pixel dy[pixel][co] * x[pixel + tap][ci]            k cut into slices
+// The per-channel affine that follows each convolution (a BatchNorm folded to scale and shift, kept
+// trainable), the ReLU and the residual add ride in the forward product's epilogue, which also writes the
+// pre-affine output a unit above the cut keeps for the scale gradient.  Backward, one memory-bound kernel per
+// convolution turns the incoming gradient into dy and the scale/shift gradients; the shortcut's gradient
+// joins in the epilogue of the block's first input-gradient product.
+#include <algorithm>
+#include <cmath>
+
+#include "model.h"
+
+namespace spb {
+namespace {
+
+struct Conv {
+  int cin = 0, cout = 0, k = 1, stride = 1, pad = 0;
+  int in_h = 0, in_w = 0, out_h = 0, out_w = 0;
+  int cin_eff = 0;               // cin rounded up to 8 (only the stem's 3-channel input differs)
+  int w = -1, scale = -1, shift = -1;  // parameter indices
+  long long in_rows(int batch) const { return (long long)batch * in_h * in_w; }
+  long long out_rows(int batch) const { return (long long)batch * out_h * out_w; }
+  int k_total() const { return k * k * cin_eff; }
+};
+
+struct Block {
+  std::vector<Conv> convs;  // main path
+  bool has_proj = false;
+  Conv proj;
+};
+
+// Offsets of one unit's tensors in the workspace.
+struct ConvBuf { size_t y = 0, a = 0; };   // pre-affine output (kept only above the cut), post-activation output
+struct UnitBuf {
+  std::vector<ConvBuf> conv;    // main-path convolutions; the last one's `a` is the unit's output
+  ConvBuf proj;                 // projection shortcut: y = pre-affine, a = its affine output
+  size_t xpad = 0, wpad = 0, pool_out = 0, which = 0;  // stem only
+  size_t out = 0;               // the unit's output tensor
+};
+
+class ResnetModel : public Model {
+ public:
+  explicit ResnetModel(const spb_model_desc& d) {
+    dtype = DType::BF16;
+    batch_ = d.batch;
+    classes_ = d.classes;
+    const bool bottleneck = d.family == SPB_FAMILY_RESNET_BOTTLENECK;
+    auto add = [&](const std::string& name, int unit, std::vector<int64_t> shape) {
+      ParamInfo p; p.name = name; p.unit = unit; p.dtype = dtype; p.shape = std::move(shape); params.push_back(p);
+      return (int)params.size() - 1;
+    };
+    auto make_conv = [&](const std::string& conv_name, const std::string& aff_name, int unit, int cin, int cout, int k, int stride, int pad, int h, int w) {
+      Conv c;
+      c.cin = cin; c.cout = cout; c.k = k; c.stride = stride; c.pad = pad; c.in_h = h; c.in_w = w;
+      c.out_h = (h + 2 * pad - k) / stride + 1; c.out_w = (w + 2 * pad - k) / stride + 1;
+      c.cin_eff = (cin + 7) / 8 * 8;
+      c.w = add(conv_name + ".weight", unit, {cout, k, k, cin});
+      c.scale = add(aff_name + ".scale", unit, {cout});
+      c.shift = add(aff_name + ".shift", unit, {cout});
+      return c;
+    };
+    stem_ = make_conv("stem.conv", "stem.aff", 0, d.image_c, d.stem_width, d.stem_kernel, d.stem_stride, d.stem_pad, d.image_h, d.image_w);
+    pool_ = d.stem_pool != 0;
+    int h = stem_.out_h, w = stem_.out_w, cin = d.stem_width;
+    if (pool_) { h = (h - 1) / 2 + 1; w = (w - 1) / 2 + 1; }
+    pool_h_ = h; pool_w_ = w;
+    for (int stage = 0; stage < d.n_stages; ++stage)
+      for (int j = 0; j < d.stage_blocks[stage]; ++j) {
+        const int width = d.stage_widths[stage], stride = (stage > 0 && j == 0) ? 2 : 1, unit = (int)blocks_.size() + 1;
+        const std::string pre = "block" + std::to_string(blocks_.size()) + ".";
+        Block b;
+        if (bottleneck) {
+          const int mid = width / 4;
+          b.convs.push_back(make_conv(pre + "conv1", pre + "aff1", unit, cin, mid, 1, 1, 0, h, w));
+          b.convs.push_back(make_conv(pre + "conv2", pre + "aff2", unit, mid, mid, 3, stride, 1, h, w));
+          b.convs.push_back(make_conv(pre + "conv3", pre + "aff3", unit, mid, width, 1, 1, 0, b.convs[1].out_h, b.convs[1].out_w));
+        } else {
+          b.convs.push_back(make_conv(pre + "conv1", pre + "aff1", unit, cin, width, 3, stride, 1, h, w));
+          b.convs.push_back(make_conv(pre + "conv2", pre + "aff2", unit, width, width, 3, 1, 1, b.convs[0].out_h, b.convs[0].out_w));
+        }
+        b.has_proj = stride != 1 || cin != width;
+        if (b.has_proj) b.proj = make_conv(pre + "proj", pre + "projaff", unit, cin, width, 1, stride, 0, h, w);
+        h = b.convs.back().out_h; w = b.convs.back().out_w; cin = width;
+        blocks_.push_back(b);
+      }
+    final_h_ = h; final_w_ = w; features_ = cin;
+    num_units = (int)blocks_.size() + 2;
+    fc_w_ = add("head.fc.weight", num_units - 1, {classes_, features_});
+    fc_b_ = add("head.fc.bias", num_units - 1, {classes_});
+    param_ptrs.assign(params.size(), nullptr);
+    grad_ptrs.assign(params.size(), nullptr);
+  }
+
+  bool shapes_ok(std::string* why) const {
+    auto conv_ok = [&](const Conv& c, bool first) {
+      if ((c.cout % 8) || c.cout > 2048) { *why = "channel counts must be multiples of 8 and at most 2048"; return false; }
+      if (!first && c.cin % 8) { *why = "channel counts must be multiples of 8"; return false; }
+      if (c.out_h <= 0 || c.out_w <= 0 || (long long)c.out_h * c.out_w > 65535 || (long long)c.in_h * c.in_w > 65535) { *why = "feature maps must have 1..65535 pixels"; return false; }
+      if (c.k * c.k > 255 || (c.stride != 1 && c.stride != 2)) { *why = "kernel up to 15x15, stride 1 or 2"; return false; }
+      return true;
+    };
+    if (!conv_ok(stem_, true)) return false;
+    for (const Block& b : blocks_) {
+      for (const Conv& c : b.convs) if (!conv_ok(c, false)) return false;
+      if (b.has_proj && !conv_ok(b.proj, false)) return false;
+    }
+    return true;
+  }
+
+  // ---- workspace plan ----------------------------------------------------------------------------
+  struct Plan {
+    std::vector<UnitBuf> unit;   // stem, blocks
+    size_t pooled, logits, row_loss, dlogits, dpooled;
+    size_t g[8];                 // backward transients: gradients of activations
+    size_t affine_partial, wgrad_partial;
+    size_t total;
+  };
+  static constexpr int kFwdPool = 8;
+
+  size_t act_bytes(long long rows, int c) const { return (size_t)rows * c * 2; }
+  size_t max_act_bytes() const {
+    size_t m = act_bytes(stem_.in_rows(batch_), stem_.cin_eff);
+    auto see = [&](const Conv& c) { m = std::max(m, act_bytes(c.out_rows(batch_), c.cout)); };
+    see(stem_);
+    for (const Block& b : blocks_) { for (const Conv& c : b.convs) see(c); if (b.has_proj) see(b.proj); }
+    return m;
+  }
+  int wgrad_splits(const Conv& c) const {
+    const long tiles = (long)((c.cout + 127) / 128) * ((c.k_total() + 127) / 128);
+    const long k_tiles = (long)((c.out_rows(batch_) + 63) / 64);
+    long s = (512 + tiles - 1) / tiles;
+    s = std::min(s, std::max(1L, k_tiles / 4));
+    return (int)std::max(1L, std::min(s, 1024L));
+  }
+
+  Plan plan(int k) const {
+    Plan p;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    const int cut = num_units - k;
+    const size_t amax = max_act_bytes();
+    size_t pool[kFwdPool];
+    for (auto& b : pool) b = take(amax);
+    int next = 0;
+    auto transient = [&]() { size_t o = pool[next]; next = (next + 1) % kFwdPool; return o; };
+    p.unit.resize(blocks_.size() + 1);
+    // A unit's tensors are kept when the unit is above the cut; its output also when the next unit is.
+    {
+      UnitBuf& u = p.unit[0];
+      const bool keep = 0 >= cut, keep_out = keep || 1 >= cut;
+      u.conv.resize(1);
+      u.xpad = stem_.cin_eff != stem_.cin ? (keep ? take(act_bytes(stem_.in_rows(batch_), stem_.cin_eff)) : transient()) : 0;
+      u.wpad = take((size_t)stem_.cout * stem_.k * stem_.k * stem_.cin_eff * 2);
+      u.conv[0].y = keep ? take(act_bytes(stem_.out_rows(batch_), stem_.cout)) : 0;
+      const size_t a_bytes = act_bytes(stem_.out_rows(batch_), stem_.cout);
+      if (pool_) {
+        u.conv[0].a = keep ? take(a_bytes) : transient();
+        u.pool_out = keep_out ? take(act_bytes((long long)batch_ * pool_h_ * pool_w_, stem_.cout)) : transient();
+        u.which = keep ? take((size_t)batch_ * pool_h_ * pool_w_ * stem_.cout) : 0;
+        u.out = u.pool_out;
+      } else {
+        u.conv[0].a = keep_out ? take(a_bytes) : transient();
+        u.out = u.conv[0].a;
+      }
+    }
+    for (size_t i = 0; i < blocks_.size(); ++i) {
+      const Block& b = blocks_[i];
+      UnitBuf& u = p.unit[i + 1];
+      const int unit = (int)i + 1;
+      const bool keep = unit >= cut, keep_out = keep || unit + 1 >= cut;
+      u.conv.resize(b.convs.size());
+      if (b.has_proj) {
+        u.proj.y = keep ? take(act_bytes(b.proj.out_rows(batch_), b.proj.cout)) : 0;
+        u.proj.a = transient();   // only the forward pass reads the shortcut's output
+      }
+      for (size_t j = 0; j < b.convs.size(); ++j) {
+        const Conv& c = b.convs[j];
+        const size_t bytes = act_bytes(c.out_rows(batch_), c.cout);
+        const bool last = j + 1 == b.convs.size();
+        u.conv[j].y = keep ? take(bytes) : 0;
+        u.conv[j].a = (last ? keep_out : keep) ? take(bytes) : transient();
+      }
+      u.out = u.conv.back().a;
+    }
+    p.pooled = take((size_t)batch_ * features_ * 2);
+    p.logits = take((size_t)batch_ * align_up((size_t)classes_, 4) * 4);
+    p.row_loss = take((size_t)batch_ * 4);
+    p.dlogits = take((size_t)batch_ * align_up((size_t)classes_, 8) * 2);
+    p.dpooled = take((size_t)batch_ * features_ * 2);
+    for (auto& g : p.g) g = 0;
+    p.affine_partial = p.wgrad_partial = 0;
+    if (k >= 2) {
+      for (auto& g : p.g) g = take(amax);
+      size_t ap = 0, wp = 0;
+      auto see = [&](const Conv& c) {
+        ap = std::max(ap, affine_partial_floats(c.out_rows(batch_), c.cout) * 4);
+        wp = std::max(wp, (size_t)wgrad_splits(c) * c.cout * c.k_total() * 4);
+      };
+      see(stem_);
+      for (const Block& b : blocks_) { for (const Conv& c : b.convs) see(c); if (b.has_proj) see(b.proj); }
+      p.affine_partial = take(ap);
+      p.wgrad_partial = take(wp);
+    }
+    p.total = off;
+    return p;
+  }
+
+  size_t workspace_size(int k) const override { return plan(k).total; }
+
+  // ---- products ----------------------------------------------------------------------------------
+  ConvGeom geom(const Conv& c) const {
+    ConvGeom g;
+    g.n = batch_; g.sh = c.in_h; g.sw = c.in_w; g.sc = c.cin_eff; g.rh = c.out_h; g.rw = c.out_w;
+    g.r = c.k; g.s = c.k; g.stride = c.stride; g.pad = c.pad; g.transposed = 0;
+    return g;
+  }
+
+  // out = act(scale * conv(x, w) + shift + residual); y_keep (optional) receives the pre-affine output
+  int conv_forward(const Conv& c, const void* x, const void* w, void* y_keep, const void* residual, bool relu, void* out, hipStream_t s) {
+    GemmProblem g;
+    g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::RowK; g.epilogue = Epilogue::BiasAct;
+    g.a_gather = Gather::ConvRows; g.conv = geom(c);
+    g.M = (int)c.out_rows(batch_); g.N = c.cout; g.K = c.k_total();
+    g.A = x; g.lda = g.K; g.B = w; g.ldb = g.K; g.C = out; g.ldc = c.cout;
+    g.col_scale = param_ptrs[c.scale]; g.bias = param_ptrs[c.shift];
+    g.aux_out = y_keep; g.ldaux = c.cout; g.aux_raw = 1;
+    g.residual = residual; g.ldres = c.cout;
+    g.act = relu ? Act::Relu : Act::None;
+    g.name = "conv_fwd";
+    return gemm(g, s);
+  }
+  // dx = conv_transpose(dy, w) + residual
+  int conv_dgrad(const Conv& c, const void* dy, const void* w, const void* residual, void* dx, hipStream_t s) {
+    GemmProblem g;
+    g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::KRow; g.epilogue = Epilogue::BiasAct;
+    g.a_gather = Gather::ConvRows; g.b_gather = Gather::ConvWeightT;
+    g.conv.n = batch_; g.conv.sh = c.out_h; g.conv.sw = c.out_w; g.conv.sc = c.cout; g.conv.rh = c.in_h; g.conv.rw = c.in_w;
+    g.conv.r = c.k; g.conv.s = c.k; g.conv.stride = c.stride; g.conv.pad = c.pad; g.conv.transposed = 1;
+    g.conv.w_cin = c.cin_eff; g.conv.w_cout = c.cout;
+    g.M = (int)c.in_rows(batch_); g.N = c.cin_eff; g.K = c.k * c.k * c.cout;
+    g.A = dy; g.lda = g.K; g.B = w; g.ldb = c.cin_eff; g.C = dx; g.ldc = c.cin_eff;
+    g.residual = residual; g.ldres = c.cin_eff;
+    g.name = "conv_dgrad";
+    return gemm(g, s);
+  }
+  // dw = sum over pixels of dy (x) x-patch, as k-slices added up in a fixed order
+  int conv_wgrad(const Conv& c, const void* x, const void* dy, float* partial, float* dw, hipStream_t s) {
+    GemmProblem g;
+    g.dtype = dtype; g.a_layout = Layout::KRow; g.b_layout = Layout::KRow; g.epilogue = Epilogue::StoreF32;
+    g.b_gather = Gather::ConvPatchT; g.conv = geom(c);
+    g.M = c.cout; g.N = c.k_total(); g.K = (int)c.out_rows(batch_);
+    g.A = dy; g.lda = c.cout; g.B = x; g.ldb = g.N; g.C = partial; g.ldc = g.N;
+    g.k_splits = wgrad_splits(c);
+    g.name = "conv_wgrad";
+    if (int rc = gemm(g, s)) return rc;
+    const long long numel = (long long)c.cout * c.k * c.k * c.cin;
+    return run("splitk_reduce", (double)(g.k_splits + 1) * numel * 4, s, [&] {
+      return launch_splitk_reduce(partial, g.k_splits, (long long)c.cout * g.N, dw, numel, c.cin, c.cin_eff, s); });
+  }
+  // gradient at the affine's output -> dy, dscale, dshift (and the masked gradient itself, if asked for)
+  int affine_bwd(const Conv& c, const void* dout, const void* act, const void* y, void* dy, void* dsum, float* partial, hipStream_t s) {
+    const long long rows = c.out_rows(batch_);
+    return run("affine_relu_bwd", (double)rows * c.cout * 2 * (3 + (act ? 1 : 0) + (dsum ? 1 : 0)), s, [&] {
+      return launch_affine_relu_bwd(dout, act, y, param_ptrs[c.scale], dy, dsum, partial, static_cast<float*>(grad_ptrs[c.scale]),
+                                    static_cast<float*>(grad_ptrs[c.shift]), rows, c.cout, s); });
+  }
+
+  int forward(const void* x, const int32_t* labels, const int32_t*, int k, void* wsp, float* loss_out, hipStream_t s) override {
+    const Plan p = plan(k);
+    char* w = static_cast<char*>(wsp);
+    const int cut = num_units - k;
+    auto keep_ptr = [&](bool keep, size_t off) -> void* { return keep ? w + off : nullptr; };
+    // ---- stem ----
+    const UnitBuf& su = p.unit[0];
+    const void* stem_in = x;
+    const void* stem_w = param_ptrs[stem_.w];
+    if (stem_.cin_eff != stem_.cin) {
+      if (int rc = run("pad_channels", (double)stem_.in_rows(batch_) * (stem_.cin + stem_.cin_eff) * 2, s, [&] {
+            return launch_pad_channels(x, w + su.xpad, stem_.in_rows(batch_), stem_.cin, stem_.cin_eff, s); })) return rc;
+      if (int rc = run("pad_channels", 0.0, s, [&] {
+            return launch_pad_channels(param_ptrs[stem_.w], w + su.wpad, (long long)stem_.cout * stem_.k * stem_.k, stem_.cin, stem_.cin_eff, s); })) return rc;
+      stem_in = w + su.xpad; stem_w = w + su.wpad;
+    }
+    x_ = stem_in == x ? x : nullptr;
+    if (int rc = conv_forward(stem_, stem_in, stem_w, keep_ptr(0 >= cut, su.conv[0].y), nullptr, true, w + su.conv[0].a, s)) return rc;
+    if (pool_) {
+      if (int rc = run("maxpool_fwd", (double)stem_.out_rows(batch_) * stem_.cout * 2 * 1.25, s, [&] {
+            return launch_maxpool_fwd(w + su.conv[0].a, w + su.pool_out, 0 >= cut ? reinterpret_cast<uint8_t*>(w + su.which) : nullptr,
+                                      batch_, stem_.out_h, stem_.out_w, stem_.cout, s); })) return rc;
+    }
+    const void* cur = w + su.out;
+    // ---- residual blocks ----
+    for (size_t i = 0; i < blocks_.size(); ++i) {
+      const Block& b = blocks_[i];
+      const UnitBuf& u = p.unit[i + 1];
+      const bool keep = (int)i + 1 >= cut;
+      const void* shortcut = cur;
+      if (b.has_proj) {
+        if (int rc = conv_forward(b.proj, cur, param_ptrs[b.proj.w], keep_ptr(keep, u.proj.y), nullptr, false, w + u.proj.a, s)) return rc;
+        shortcut = w + u.proj.a;
+      }
+      const void* h = cur;
+      for (size_t j = 0; j < b.convs.size(); ++j) {
+        const bool last = j + 1 == b.convs.size();
+        if (int rc = conv_forward(b.convs[j], h, param_ptrs[b.convs[j].w], keep_ptr(keep, u.conv[j].y), last ? shortcut : nullptr, true,
+                                  w + u.conv[j].a, s)) return rc;
+        h = w + u.conv[j].a;
+      }
+      cur = h;
+    }
+    // ---- head ----
+    const int hw = final_h_ * final_w_;
+    if (int rc = run("avgpool_fwd", (double)batch_ * hw * features_ * 2, s, [&] { return launch_avgpool_fwd(cur, w + p.pooled, batch_, hw, features_, s); })) return rc;
+    const int ldz = (int)align_up((size_t)classes_, 4), lddz = (int)align_up((size_t)classes_, 8);
+    {
+      GemmProblem g;
+      g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::RowK; g.epilogue = Epilogue::StoreF32;
+      g.M = batch_; g.N = classes_; g.K = features_; g.A = w + p.pooled; g.lda = features_; g.B = param_ptrs[fc_w_]; g.ldb = features_;
+      g.bias = param_ptrs[fc_b_]; g.C = w + p.logits; g.ldc = ldz; g.name = "gemm_bf16_fwd_logits";
+      if (int rc = gemm(g, s)) return rc;
+    }
+    return run("softmax_xent", (double)batch_ * classes_ * 6, s, [&] {
+      return launch_softmax_xent(reinterpret_cast<const float*>(w + p.logits), ldz, labels, batch_, classes_, w + p.dlogits, lddz, dtype,
+                                 reinterpret_cast<float*>(w + p.row_loss), loss_out, s); });
+  }
+
+  int backward(int k, hipStream_t s) override {
+    const Plan p = plan(stashed_k);
+    char* w = static_cast<char*>(ws);
+    const int cut = num_units - k;
+    const int lddz = (int)align_up((size_t)classes_, 8), hw = final_h_ * final_w_;
+    float* apart = reinterpret_cast<float*>(w + p.affine_partial);
+    float* wpart = reinterpret_cast<float*>(w + p.wgrad_partial);
+    // ---- head ----
+    {
+      GemmProblem g;  // dW = dlogits^T pooled; db = column sums
+      g.dtype = dtype; g.a_layout = Layout::KRow; g.b_layout = Layout::KRow; g.epilogue = Epilogue::StoreF32;
+      g.M = classes_; g.N = features_; g.K = batch_; g.A = w + p.dlogits; g.lda = lddz; g.B = w + p.pooled; g.ldb = features_;
+      g.C = grad_ptrs[fc_w_]; g.ldc = features_; g.a_row_sum = static_cast<float*>(grad_ptrs[fc_b_]); g.a_pad_zero = g.b_pad_zero = true;
+      g.name = "gemm_bf16_wgrad";
+      if (int rc = gemm(g, s)) return rc;
+    }
+    if (cut >= num_units - 1) return SPB_OK;  // the head was the lowest unit: no input gradient
+    {
+      GemmProblem g;  // dpooled = dlogits W
+      g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::KRow; g.epilogue = Epilogue::BiasAct;
+      g.M = batch_; g.N = features_; g.K = classes_; g.A = w + p.dlogits; g.lda = lddz; g.B = param_ptrs[fc_w_]; g.ldb = features_;
+      g.C = w + p.dpooled; g.ldc = features_; g.a_pad_zero = g.b_pad_zero = true; g.name = "gemm_bf16_dgrad";
+      if (int rc = gemm(g, s)) return rc;
+    }
+    void* dout = w + p.g[0];
+    int dout_slot = 0;
+    if (int rc = run("avgpool_bwd", (double)batch_ * hw * features_ * 2, s, [&] { return launch_avgpool_bwd(w + p.dpooled, dout, batch_, hw, features_, s); })) return rc;
+    // ---- residual blocks, top down ----
+    for (int i = (int)blocks_.size() - 1; i >= 0 && i + 1 >= cut; --i) {
+      const Block& b = blocks_[i];
+      const UnitBuf& u = p.unit[i + 1];
+      const bool need_dx = i + 1 > cut;
+      const void* x_in = w + p.unit[i].out;
+      void* dsum = w + p.g[2];
+      void* dy = w + p.g[3];
+      void* da = w + p.g[4];
+      const int last = (int)b.convs.size() - 1;
+      // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut
+      if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart, s)) return rc;
+      for (int j = last; j >= 1; --j) {
+        const void* in_j = w + u.conv[j - 1].a;
+        if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[j].w]), s)) return rc;
+        if (int rc = conv_dgrad(b.convs[j], dy, param_ptrs[b.convs[j].w], nullptr, da, s)) return rc;
+        void* dy_next = w + p.g[j % 2 ? 5 : 3];
+        if (int rc = affine_bwd(b.convs[j - 1], da, in_j, w + u.conv[j - 1].y, dy_next, nullptr, apart, s)) return rc;
+        dy = dy_next;
+      }
+      if (int rc = conv_wgrad(b.convs[0], x_in, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[0].w]), s)) return rc;
+      const void* shortcut_grad = dsum;
+      if (b.has_proj) {
+        void* dys = w + p.g[6];
+        if (int rc = affine_bwd(b.proj, dsum, nullptr, w + u.proj.y, dys, nullptr, apart, s)) return rc;
+        if (int rc = conv_wgrad(b.proj, x_in, dys, wpart, static_cast<float*>(grad_ptrs[b.proj.w]), s)) return rc;
+        if (need_dx) {
+          if (int rc = conv_dgrad(b.proj, dys, param_ptrs[b.proj.w], nullptr, w + p.g[7], s)) return rc;
+          shortcut_grad = w + p.g[7];
+        }
+      }
+      if (!need_dx) return SPB_OK;  // lowest unit: no input gradient
+      void* dx = w + p.g[dout_slot ^ 1];
+      if (int rc = conv_dgrad(b.convs[0], dy, param_ptrs[b.convs[0].w], shortcut_grad, dx, s)) return rc;
+      dout = dx;
+      dout_slot ^= 1;
+    }
+    // ---- stem (unit 0), reached only at full depth ----
+    if (cut == 0) {
+      const UnitBuf& su = p.unit[0];
+      const void* d = dout;
+      if (pool_) {
+        if (int rc = run("maxpool_bwd", (double)stem_.out_rows(batch_) * stem_.cout * 2 * 1.5, s, [&] {
+              return launch_maxpool_bwd(dout, reinterpret_cast<const uint8_t*>(w + su.which), w + p.g[4], batch_, stem_.out_h, stem_.out_w, stem_.cout, s); })) return rc;
+        d = w + p.g[4];
+      }
+      if (int rc = affine_bwd(stem_, d, w + su.conv[0].a, w + su.conv[0].y, w + p.g[3], nullptr, apart, s)) return rc;
+      const void* stem_in = stem_.cin_eff != stem_.cin ? (const void*)(w + su.xpad) : x_;
+      if (int rc = conv_wgrad(stem_, stem_in, w + p.g[3], wpart, static_cast<float*>(grad_ptrs[stem_.w]), s)) return rc;
+    }
+    return SPB_OK;
+  }
+
+ private:
+  int batch_ = 0, classes_ = 0, features_ = 0, final_h_ = 0, final_w_ = 0, pool_h_ = 0, pool_w_ = 0;
+  bool pool_ = false;
+  Conv stem_;
+  std::vector<Block> blocks_;
+  int fc_w_ = -1, fc_b_ = -1;
+  const void* x_ = nullptr;
+};
+
+}  // namespace
+
+std::unique_ptr<Model> make_resnet(const spb_model_desc& d) {
+  if (d.dtype != SPB_DTYPE_BF16) { set_error("resnet: only bfloat16 storage is built"); return nullptr; }
+  if (d.image_h <= 0 || d.image_w <= 0 || d.image_c <= 0 || d.image_c > 8 || d.stem_kernel <= 0 || d.stem_width <= 0 || d.classes <= 0 ||
+      d.n_stages <= 0 || d.n_stages > SPB_MAX_STAGES || d.stem_pad < 0) {
+    set_error("resnet: image (up to 8 channels), stem, stages and classes must be positive");
+    return nullptr;
+  }
+  for (int i = 0; i < d.n_stages; ++i)
+    if (d.stage_blocks[i] <= 0 || d.stage_widths[i] <= 0 || (d.family == SPB_FAMILY_RESNET_BOTTLENECK && d.stage_widths[i] % 32)) {
+      set_error("resnet: stage %d needs blocks > 0 and a positive width (a multiple of 32 for bottlenecks)", i);
+      return nullptr;
+    }
+  auto m = std::make_unique<ResnetModel>(d);
+  std::string why;
+  if (!m->shapes_ok(&why)) { set_error("resnet: %s", why.c_str()); return nullptr; }
+  return m;
+}
+
+}  // namespace spb
