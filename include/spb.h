@@ -177,6 +177,13 @@ int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream);
 int spb_set_kernel_timing(spb_model* m, int32_t enable);
 int spb_read_kernel_timing(spb_model* m, spb_kernel_time* out, int32_t cap, int32_t* n_out);
 
+/* Measurement aid: enqueue `count` back-to-back copies of the most recent matrix product of kernel class
+ * `name` (e.g. "gemm_bf16_fwd") that ran while timing was enabled, on the same operands (the workspace of the
+ * last step must still be alive; the copies rewrite that product's output with the same values).  Two events
+ * around the call give the kernel's duration without the per-launch event overhead.
+ * Errors: INVALID_ARG, STATE (no such product recorded), HIP. */
+int spb_replay_kernel(spb_model* m, const char* name, int32_t count, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -64,6 +64,7 @@ EXPORTS = {
     "spb_grad_buffers": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spb_grad_view), C.c_int32, C.POINTER(C.c_int32)]),
     "spb_zero_absent_grads": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "spb_set_kernel_timing": (C.c_int, [C.c_void_p, C.c_int32]),
+    "spb_replay_kernel": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int32, C.c_void_p]),
     "spb_read_kernel_timing": (C.c_int, [C.c_void_p, C.POINTER(spb_kernel_time), C.c_int32, C.POINTER(C.c_int32)]),
 }
 
@@ -200,6 +201,10 @@ def spb_zero_absent_grads(m, k, stream):
 
 def spb_set_kernel_timing(m, enable: bool):
     _check(lib().spb_set_kernel_timing(m, int(enable)))
+
+
+def spb_replay_kernel(m, name: str, count: int, stream):
+    _check(lib().spb_replay_kernel(m, name.encode(), count, C.c_void_p(stream)))
 
 
 def spb_read_kernel_timing(m, cap=64):

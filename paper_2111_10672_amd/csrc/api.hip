@@ -24,7 +24,16 @@ int Model::check(hipError_t e, const char* what) {
   return SPB_ERR_HIP;
 }
 
+int Model::replay(const char* name, int count, hipStream_t s) {
+  auto it = last_product.find(name);
+  if (it == last_product.end()) { set_error("spb_replay_kernel: no product of class %s has run with timing enabled", name); return SPB_ERR_STATE; }
+  for (int i = 0; i < count; ++i)
+    if (int rc = check(launch_gemm(it->second, s), name)) return rc;
+  return SPB_OK;
+}
+
 int Model::gemm(const GemmProblem& p, hipStream_t s) {
+  if (timer.enabled()) last_product[p.name] = p;
   hipError_t e = timer.run(p.name, gemm_flops(p), gemm_bytes(p), s, [&] { return launch_gemm(p, s); });
   return check(e, p.name);
 }
@@ -260,6 +269,11 @@ int spb_set_kernel_timing(spb_model* m, int32_t enable) {
   SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_set_kernel_timing: null model");
   m->impl->timer.enable(enable != 0);
   return SPB_OK;
+}
+
+int spb_replay_kernel(spb_model* m, const char* name, int32_t count, void* stream) {
+  SPB_REQUIRE(m && name && count > 0, SPB_ERR_INVALID_ARG, "spb_replay_kernel: null argument or non-positive count");
+  return m->impl->replay(name, count, static_cast<hipStream_t>(stream));
 }
 
 int spb_read_kernel_timing(spb_model* m, spb_kernel_time* out, int32_t cap, int32_t* n_out) {

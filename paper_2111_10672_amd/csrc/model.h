@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <functional>
+#include <map>
 #include <memory>
 #include <string>
 #include <vector>
@@ -61,6 +62,8 @@ class Model {
   int stashed_k = -1;  // depth the last forward pass stashed for; -1 = no forward yet
   void* ws = nullptr;
   KernelTimer timer;
+  std::map<std::string, GemmProblem> last_product;  // per kernel class, the most recent product (kept while timing is on)
+  int replay(const char* name, int count, hipStream_t s);
 
  protected:
   int gemm(const GemmProblem& p, hipStream_t s);
