@@ -20,7 +20,7 @@ pytestmark = pytest.mark.gpu
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
-@pytest.mark.parametrize("name", ["cfg3", "cfg5"])
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
 def test_full_size_depth_sweep_against_golden_samples(name):
     seed = 0
     with open(os.path.join(GOLDEN, f"{name}_seed{seed}.json")) as f:
