@@ -18,17 +18,33 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
+FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
+         # hipcc -O3 would otherwise form packed float32 instructions from scalar code
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-I" + os.path.join(ROOT, "include")]
+
+
+def _compile(src: str, obj: str):
+    return subprocess.run([hipcc(), *FLAGS, "-c", src, "-o", obj], capture_output=True, text=True)
+
+
 def build_library(verbose: bool = False) -> str:
+    """Compile every csrc/*.hip (one process per file, side by side) and link libspb.so."""
+    from concurrent.futures import ThreadPoolExecutor
     sources = sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
-    cmd = [hipcc(), "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
-           # hipcc -O3 would otherwise form packed float32 instructions from scalar code
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I" + os.path.join(ROOT, "include"), *sources, "-o", LIB + ".tmp"]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if verbose or res.returncode:
-        print(res.stdout, res.stderr)
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in sources]
+    with ThreadPoolExecutor(max_workers=min(8, len(sources))) as pool:
+        results = list(pool.map(_compile, sources, objs))
+    for src, res in zip(sources, results):
+        if verbose or res.returncode:
+            print(src, res.stdout, res.stderr)
+        if res.returncode:
+            raise RuntimeError(f"hipcc failed on {src}:\n" + res.stderr[-4000:])
+    res = subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB + ".tmp"], capture_output=True, text=True)
     if res.returncode:
-        raise RuntimeError("hipcc failed:\n" + res.stderr[-4000:])
+        raise RuntimeError("link failed:\n" + res.stderr[-4000:])
     os.replace(LIB + ".tmp", LIB)
     return LIB
 

@@ -82,15 +82,20 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
   }
 }
 
-// out[c] sums: same layout as the LayerNorm partials ([blocks][2][width]); blocks added in index order.
+// out_a[c] = sum_b partial[b][0][c], out_b[c] = sum_b partial[b][1][c].  One wavefront per column: lane l adds blocks
+// l, l + 64, ... in order, then the 64 lane sums are combined by a fixed shuffle tree (same bits on every run).
 __global__ __launch_bounds__(256) void reduce_pairs_kernel(const float* __restrict__ partial, int n_blocks, int width,
                                                            float* __restrict__ out_a, float* __restrict__ out_b) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63, col = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (col >= 2 * width) return;
   float s = 0.f;
-  for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * 2 * width + col];
-  if (col < width) out_a[col] = s;
-  else out_b[col - width] = s;
+  for (int b = lane; b < n_blocks; b += 64) s += partial[(size_t)b * 2 * width + col];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) {
+    if (col < width) out_a[col] = s;
+    else out_b[col - width] = s;
+  }
 }
 
 // out[j] = sum over slices of partial[slice][map(j)], slices added in index order; map drops padded input channels.
@@ -208,7 +213,7 @@ hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void*
                      (const uint16_t*)scale, (uint16_t*)dy, (uint16_t*)dsum, partial, rows, channels, rpb);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_pairs_kernel, dim3((2 * channels + 255) / 256), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
+  hipLaunchKernelGGL(reduce_pairs_kernel, dim3((2 * channels + 3) / 4), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
   return hipGetLastError();
 }
 

@@ -1,0 +1,471 @@
+// bfloat16 products on the gfx950 matrix cores with direct-to-LDS operand loads.
+//
+//   C[m, n] = sum_k A(m, k) * B(n, k),   float32 accumulation
+//
+// Same three products as gemm.hip (forward, input gradient, weight gradient of a dense layer), built
+// around two CDNA4 facilities:
+//   * global_load_lds_dwordx4: every lane fetches 16 bytes from its own global address and the wave's
+//     64 chunks land in one contiguous KiB of LDS, without passing through registers.  Several tiles
+//     can therefore be in flight at once (STAGES-deep ring); which chunk a lane fetches is chosen so
+//     that the KiB it fills is already in the bank-friendly order the matrix-core reads want.
+//   * ds_read_b64_tr_b16: a transposing LDS read.  An operand whose *row* index is contiguous in memory
+//     (the layout of both weight-gradient operands and of W in the input-gradient product) is copied to
+//     LDS as it lies and transposed on the way to the registers.  Within 16 lanes, lane j receives
+//     element (j % 4) of the 8-byte words read by lanes j/4, j/4 + 4, j/4 + 8, j/4 + 12; pointing lane j'
+//     at 4 consecutive rows starting at row 4 * (j' % 4) of k-row j'/4 gives lane j four consecutive k
+//     of row j, which is the MFMA operand layout.
+// Tile loop: wait for tile t (s_waitcnt vmcnt leaves the younger tiles' loads in flight), one barrier,
+// issue tile t + STAGES - 1 into the buffer tile t - 1 used, multiply tile t.
+#pragma once
+#include "gemm_common.h"
+
+namespace spb {
+namespace gemm_dma_detail {
+using namespace gemm_detail;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* global_ptr_t;
+
+static __device__ const uint32_t kZeroChunk[4] = {0u, 0u, 0u, 0u};
+
+constexpr int kTileK = 64;  // bfloat16 elements of k per tile: 128 bytes per row
+
+// s_waitcnt immediate for gfx9: vmcnt in bits 3:0 and 15:14, expcnt 6:4 (7 = no wait), lgkmcnt 11:8.
+constexpr int waitcnt_imm(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | (7 << 4) | ((lgkm & 15) << 8); }
+
+template <int VM>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM, 0));
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Rotation (in 16-byte chunks) of k-row k of a KRow tile, so that the four k-rows one transposing read
+// touches fall into different 64-byte bank groups.
+template <int ROWS>
+__device__ __forceinline__ int krow_rot(int k) {
+  if constexpr (ROWS >= 128) return (k & 3) << 2;
+  else if constexpr (ROWS == 64) return ((k >> 1) & 1) << 2;
+  else return 0;
+}
+
+// Where one lane's 16-byte chunks of an operand tile come from.  Everything that does not change from
+// tile to tile is worked out once; tiles are issued in increasing order, so what does change (the tap and
+// channel a chunk's k falls on, the pixel a k-row stands for) is stepped, never divided out again.
+// Every wave issues exactly kInstr direct-to-LDS instructions per tile, whatever its lanes' predicates:
+// a lane outside the matrix (or in a convolution's zero padding) fetches a chunk of zeros instead, so the
+// vmcnt arithmetic of the tile loop holds and rows or k beyond the matrix multiply as zero.
+template <int ROWS, Layout L, Gather G, int NW>
+struct TileSource {
+  static constexpr int kInstr = ROWS / (8 * NW);
+  static_assert(ROWS % (8 * NW) == 0 && kInstr >= 1, "tile rows must fill whole wave instructions");
+  static_assert(G == Gather::None || (G == Gather::ConvRows) == (L == Layout::RowK), "gather kind fixes the LDS layout");
+  const char* ptr[kInstr];  // Plain: this lane's chunk in tile 0.  Gathers: the tensor's base.
+  int k_in_tile[kInstr];    // k of the chunk's first element relative to the tile start
+  bool in_rows[kInstr];
+  int row_idx[kInstr];      // first row (of the operand) this lane's chunk covers
+  size_t tile_step;         // Plain: bytes from one tile to the next
+  // gather state, per instruction
+  int tap[kInstr], chan[kInstr];           // ConvRows, ConvWeightT: where this lane's k of the next tile falls; ConvPatchT: fixed (tap, ci) of its rows
+  int g0[kInstr], g1[kInstr], g2[kInstr];  // ConvRows: pixel base, row term, column term.  ConvPatchT: image, pixel in image of the next tile's k-row.
+  int step_q, step_r;                      // one tile further: quotient and remainder of 64 by the modulus being stepped
+
+  __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int wave, int lane, int t0, const ConvGeom& cg) {
+    tile_step = L == Layout::RowK ? (size_t)kTileK * 2 : (size_t)kTileK * ld * 2;
+    const int modulus = G == Gather::ConvRows ? cg.sc : G == Gather::ConvWeightT ? cg.w_cout : cg.rh * cg.rw;
+    if constexpr (G != Gather::None) { step_q = kTileK / modulus; step_r = kTileK % modulus; }
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const int slot = (i * NW + wave) * 64 + lane;
+      int gr, k;
+      if constexpr (L == Layout::RowK) {
+        const int row = slot >> 3, pc = slot & 7;
+        gr = row0 + row;
+        k = ((pc ^ row ^ (row >> 3)) & 7) << 3;
+      } else {
+        constexpr int kRowChunks = ROWS / 8;
+        k = slot / kRowChunks;
+        const int pc = slot % kRowChunks;
+        gr = row0 + (((pc - krow_rot<ROWS>(k)) & (kRowChunks - 1)) << 3);
+      }
+      k_in_tile[i] = k;
+      in_rows[i] = gr < nrows;
+      row_idx[i] = gr;
+      if constexpr (G == Gather::None) {
+        ptr[i] = reinterpret_cast<const char*>(L == Layout::RowK ? base + (size_t)gr * ld + k : base + (size_t)k * ld + gr) + (size_t)t0 * tile_step;
+      } else {
+        ptr[i] = reinterpret_cast<const char*>(base);
+        const int k_abs = t0 * kTileK + k;
+        if constexpr (G == Gather::ConvRows) {        // row gr = pixel (n, a, b); k = (tap, channel)
+          const int per_image = cg.rh * cg.rw;
+          const int n = gr / per_image, rem = gr - n * per_image;
+          const int a = rem / cg.rw, b = rem - a * cg.rw;
+          g0[i] = n * cg.sh * cg.sw;
+          g1[i] = cg.transposed ? a + cg.pad : a * cg.stride - cg.pad;
+          g2[i] = cg.transposed ? b + cg.pad : b * cg.stride - cg.pad;
+          tap[i] = k_abs / cg.sc; chan[i] = k_abs - tap[i] * cg.sc;
+        } else if constexpr (G == Gather::ConvWeightT) {  // row gr = ci; k = (tap, co)
+          tap[i] = k_abs / cg.w_cout; chan[i] = k_abs - tap[i] * cg.w_cout;
+        } else {                                          // row gr = (tap, ci); k = output pixel m
+          tap[i] = gr / cg.sc; chan[i] = gr - tap[i] * cg.sc;
+          const int per_image = cg.rh * cg.rw;
+          g0[i] = k_abs / per_image; g1[i] = k_abs - g0[i] * per_image; g2[i] = 0;
+        }
+      }
+    }
+  }
+
+  // Issue tile t (tiles must be issued in increasing order, one after the other).
+  __device__ __forceinline__ void issue(int t, int K, char* tile, int wave, int ld, const ConvGeom& cg) {
+#pragma unroll
+    for (int i = 0; i < kInstr; ++i) {
+      const char* src = reinterpret_cast<const char*>(kZeroChunk);
+      if constexpr (G == Gather::None) {
+        if (in_rows[i] && t * kTileK + k_in_tile[i] < K) src = ptr[i];
+        ptr[i] += tile_step;
+      } else if constexpr (G == Gather::ConvRows) {
+        const int taps = cg.r * cg.s;
+        const int r = (tap[i] * (65536 / cg.s + 1)) >> 16, c = tap[i] - r * cg.s;   // tap = r * S + c, exact for tap < 256
+        int hi, wi;
+        bool ok = in_rows[i] && tap[i] < taps;
+        if (!cg.transposed) {
+          hi = g1[i] + r; wi = g2[i] + c;
+        } else {
+          const int th = g1[i] - r, tw = g2[i] - c, m = cg.stride - 1;   // stride is 1 or 2
+          ok = ok && th >= 0 && tw >= 0 && ((th | tw) & m) == 0;
+          hi = th >> m; wi = tw >> m;
+        }
+        ok = ok && (unsigned)hi < (unsigned)cg.sh && (unsigned)wi < (unsigned)cg.sw;
+        if (ok) src = ptr[i] + ((size_t)(g0[i] + hi * cg.sw + wi) * cg.sc + chan[i]) * 2;
+        chan[i] += step_r; tap[i] += step_q;
+        if (chan[i] >= cg.sc) { chan[i] -= cg.sc; ++tap[i]; }
+      } else if constexpr (G == Gather::ConvWeightT) {
+        const int taps = cg.r * cg.s;
+        if (in_rows[i] && tap[i] < taps) src = ptr[i] + (((size_t)chan[i] * taps + tap[i]) * cg.w_cin + row_idx[i]) * 2;
+        chan[i] += step_r; tap[i] += step_q;
+        if (chan[i] >= cg.w_cout) { chan[i] -= cg.w_cout; ++tap[i]; }
+      } else {
+        const int r = (tap[i] * (65536 / cg.s + 1)) >> 16, c = tap[i] - r * cg.s;
+        const int oh = __float2int_rz(((float)g1[i] + 0.5f) * (1.0f / (float)cg.rw)), ow = g1[i] - oh * cg.rw;
+        const int hi = oh * cg.stride + r - cg.pad, wi = ow * cg.stride + c - cg.pad;
+        if (in_rows[i] && g0[i] < cg.n && (unsigned)hi < (unsigned)cg.sh && (unsigned)wi < (unsigned)cg.sw)
+          src = ptr[i] + ((size_t)((g0[i] * cg.sh + hi) * cg.sw + wi) * cg.sc + chan[i]) * 2;
+        const int per_image = cg.rh * cg.rw;
+        g1[i] += step_r; g0[i] += step_q;
+        if (g1[i] >= per_image) { g1[i] -= per_image; ++g0[i]; }
+      }
+      __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, 0, 0);
+    }
+  }
+
+};
+
+// Fetch the MFMA operand of one 32-row fragment for k-group kg (16 values of k): 8 bfloat16 per lane.
+// A KRow fragment is read in assembly and is valid only after fragments_ready().
+template <int ROWS, Layout L>
+__device__ __forceinline__ u32x4 read_fragment(const char* tile, int frag_row0, int kg, int lane) {
+  if constexpr (L == Layout::RowK) {
+    return *reinterpret_cast<const u32x4*>(tile + lds_offset(frag_row0 + (lane & 31), 2 * kg + (lane >> 5)));
+  } else {
+    constexpr int kRowChunks = ROWS / 8;
+    const int j = lane & 15, g = lane >> 4;
+    const int row = frag_row0 + 16 * (g & 1) + 4 * (j & 3);  // first of the 4 rows this lane's word covers
+    u32x4 out;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k = 16 * kg + 8 * (g >> 1) + 4 * h + (j >> 2);
+      const int pc = ((row >> 3) + krow_rot<ROWS>(k)) & (kRowChunks - 1);
+      const char* addr = tile + k * (ROWS * 2) + pc * 16 + (row & 7) * 2;
+      // Written as assembly: through the builtin the compiler cannot tell this read from the in-flight
+      // direct-to-LDS tiles and drains them all (vmcnt 0) first.
+      const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)addr;
+      uint2 w;
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(w) : "v"(lds_addr));
+      out[2 * h] = w.x;
+      out[2 * h + 1] = w.y;
+    }
+    return out;
+  }
+}
+
+// Wait for the LDS reads issued in assembly and pin every later use of the fragments behind the wait.
+template <int NA, int NB>
+__device__ __forceinline__ void fragments_ready(u32x4 (&a)[NA], u32x4 (&b)[NB]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < NA; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+  for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xFFFF0000u);
+}
+
+// Epilogue.  Each wave parks 32 rows of its WM x WN accumulator tile at a time in its own LDS region (the tile
+// ring is dead by then) and reads them back row by row, so that bias, mask and result move in 16-byte pieces
+// along n.  LDS operations of one wave complete in order, so the pieces need no barrier between them.
+template <int WM, int WN>
+__device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage,
+                                                int row_base, int col_base, int lane, long long c_offset) {
+  constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of rows 4 apart
+  const bf16_t* bias = static_cast<const bf16_t*>(p.bias);
+#pragma unroll
+  for (int piece = 0; piece < WM / 32; ++piece) {
+  const int piece_row = row_base + piece * 32;
+#pragma unroll
+  for (int j = 0; j < WN / 32; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[piece][j][r];
+  if (p.epilogue == (int)Epilogue::StoreF32) {
+    constexpr int kUnits = 32 * WN / 4;
+#pragma unroll
+    for (int it = 0; it < kUnits / 64; ++it) {
+      const int u = it * 64 + lane;
+      const int row = u / (WN / 4), c = (u % (WN / 4)) * 4;
+      const int m = piece_row + row, n = col_base + c;
+      if (m >= p.M || n >= p.N) continue;
+      f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c) * p.alpha;
+      float* dst = static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n;
+      if (n + 4 <= p.N) {
+        if (bias) {
+          const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
+          v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+          v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+        }
+        *reinterpret_cast<f32x4*>(dst) = v;
+      } else {
+        for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e] + (bias ? to_float(bias[n + e]) : 0.f);
+      }
+    }
+  } else {
+    constexpr int kUnits = 32 * WN / 8;
+    const int mode = p.epilogue;  // BiasAct, MaskStore or GeluBwdStore
+    const bf16_t* mask = static_cast<const bf16_t*>(p.mask);
+    const bf16_t* res = static_cast<const bf16_t*>(p.residual);
+    bf16_t* aux = static_cast<bf16_t*>(p.aux_out);
+    auto unpack = [](const u32x4& w, float (&f)[8]) {
+#pragma unroll
+      for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
+    };
+    auto pack = [](const float (&f)[8]) {
+      u32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) o[d] = pack_bf16(f[2 * d], f[2 * d + 1]);
+      return o;
+    };
+    // one element of the epilogue, shared by the 16-byte path and the ragged tail
+    const bf16_t* cscale = static_cast<const bf16_t*>(p.col_scale);
+    // (in BiasAct mode mk carries the column scale, 1 if there is none)
+    auto finish = [&](float v, float b, float mk, float r, float& pre) {
+      if (mode == (int)Epilogue::MaskStore) return mk > 0.f ? v : 0.f;
+      if (mode == (int)Epilogue::GeluBwdStore) return v * gelu_grad_f(mk);
+      v *= p.alpha;
+      pre = v;
+      v = v * mk + b;
+      if (!p.aux_raw) pre = v;
+      v += r;                                   // a residual joins before the activation (residual blocks)
+      if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
+      else if (p.act == (int)Act::Gelu) v = gelu_f(v);
+      return v;
+    };
+#pragma unroll
+    for (int it = 0; it < kUnits / 64; ++it) {
+      const int u = it * 64 + lane;
+      const int row = u / (WN / 8), c = (u % (WN / 8)) * 8;
+      const int m = piece_row + row, n = col_base + c;
+      if (m >= p.M || n >= p.N) continue;
+      float v[8], b[8], mk[8], r[8], pre[8];
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
+      const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { b[e] = 0.f; mk[e] = 0.f; r[e] = 0.f; pre[e] = 0.f; }
+      bf16_t* dst = static_cast<bf16_t*>(p.C) + c_offset + (size_t)m * p.ldc + n;
+      if (n + 8 <= p.N) {
+        if (mode != (int)Epilogue::BiasAct) {
+          unpack(*reinterpret_cast<const u32x4*>(mask + (size_t)m * p.ldmask + n), mk);
+        } else {
+          if (cscale) unpack(*reinterpret_cast<const u32x4*>(cscale + n), mk);
+          else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mk[e] = 1.f;
+          }
+          if (bias) unpack(*reinterpret_cast<const u32x4*>(bias + n), b);
+          if (res) unpack(*reinterpret_cast<const u32x4*>(res + (size_t)m * p.ldres + n), r);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = finish(v[e], b[e], mk[e], r[e], pre[e]);
+        if (aux && mode == (int)Epilogue::BiasAct) *reinterpret_cast<u32x4*>(aux + (size_t)m * p.ldaux + n) = pack(pre);
+        *reinterpret_cast<u32x4*>(dst) = pack(v);
+      } else {
+        for (int e = 0; e < 8 && n + e < p.N; ++e) {
+          float be = 0.f, me = 0.f, re = 0.f, pe = 0.f;
+          if (mode != (int)Epilogue::BiasAct) me = to_float(mask[(size_t)m * p.ldmask + n + e]);
+          else { me = cscale ? to_float(cscale[n + e]) : 1.f; if (bias) be = to_float(bias[n + e]); if (res) re = to_float(res[(size_t)m * p.ldres + n + e]); }
+          const float x = finish(v[e], be, me, re, pe);
+          if (aux && mode == (int)Epilogue::BiasAct) store_elem(aux + (size_t)m * p.ldaux + n + e, pe);
+          store_elem(dst + e, x);
+        }
+      }
+    }
+  }
+  }  // piece
+}
+
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB, Gather GA, Gather GB>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(GemmParams p) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
+  static_assert(STAGES >= 2 && STAGES <= 8, "ring depth");
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(TM >= 1 && TN >= 1 && WM % 32 == 0 && WN % 32 == 0, "wave tile is a multiple of 32x32");
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  constexpr int kLoadsPerTile = (BM + BN) / (8 * NW);  // direct-to-LDS instructions per wave per tile
+  constexpr int kBatch = (TM + TN) <= 2 ? 4 : ((TM + TN) <= 4 ? 2 : 1);  // k-groups whose fragments are fetched together
+  static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
+  const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+
+  TileSource<BM, LA, GA, NW> src_a;
+  TileSource<BN, LB, GB, NW> src_b;
+  const int z = blockIdx.y;  // batch entry, or slice of the k range
+  int t_first = 0, n_steps = (p.K + kTileK - 1) / kTileK;
+  if (p.k_tiles_per_split > 0) {
+    t_first = z * p.k_tiles_per_split;
+    n_steps = min(n_steps, t_first + p.k_tiles_per_split);
+  }
+  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset(p.a_batch, z), p.lda, m0, p.M, wave, lane, t_first, p.conv);
+  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset(p.b_batch, z), p.ldb, n0, p.N, wave, lane, t_first, p.conv);
+  auto issue = [&](int t) {
+    char* stage = lds + ((t - t_first) % STAGES) * kStageBytes;
+    src_a.issue(t, p.K, stage, wave, p.lda, p.conv);
+    src_b.issue(t, p.K, stage + BM * kRowBytes, wave, p.ldb, p.conv);
+  };
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (t_first + s < n_steps) issue(t_first + s);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const bool want_row_sum = LA == Layout::KRow && p.a_row_sum != nullptr && tile_n == 0;
+  float row_sum = 0.f;
+
+  for (int t = t_first; t < n_steps; ++t) {
+    // Tiles t+1 .. t+STAGES-2 may stay in flight if they were all issued; near the end wait for everything.
+    if (t + STAGES - 2 < n_steps) wait_loads_and_barrier<(STAGES - 2) * kLoadsPerTile>();
+    else wait_loads_and_barrier<0>();
+    if (t + STAGES - 1 < n_steps) issue(t + STAGES - 1);
+    const char* as = lds + ((t - t_first) % STAGES) * kStageBytes;
+    const char* bs = as + BM * kRowBytes;
+#pragma unroll
+    for (int kb = 0; kb < 4; kb += kBatch) {
+      u32x4 a[kBatch * TM], b[kBatch * TN];
+#pragma unroll
+      for (int g = 0; g < kBatch; ++g) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[g * TM + i] = read_fragment<BM, LA>(as, wm * WM + i * 32, kb + g, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[g * TN + j] = read_fragment<BN, LB>(bs, wn * WN + j * 32, kb + g, lane);
+      }
+      if constexpr (LA == Layout::KRow || LB == Layout::KRow) fragments_ready(a, b);
+#pragma unroll
+      for (int g = 0; g < kBatch; ++g)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[g * TM + i]),
+                                                                __builtin_bit_cast(bf16x8, b[g * TN + j]), acc[i][j], 0, 0, 0);
+      if constexpr (LA == Layout::RowK && LB == Layout::RowK) {
+        // Keep the batch's LDS reads ahead of its MFMAs (the scheduler otherwise sinks each read to its use
+        // and the wave eats one LDS latency per MFMA).
+        __builtin_amdgcn_sched_group_barrier(0x100, kBatch * (TM + TN), 0);  // DS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, kBatch * TM * TN, 0);    // MFMA
+      }
+    }
+    if constexpr (LA == Layout::KRow) {
+      if (want_row_sum && threadIdx.x < BM) {  // bias gradient: sum over k of A(row, k), tile rows lie along the LDS row
+        const int row = threadIdx.x;
+#pragma unroll 8
+        for (int k = 0; k < kTileK; ++k) {
+          const int pc = ((row >> 3) + krow_rot<BM>(k)) & (BM / 8 - 1);
+          const uint16_t bits = *reinterpret_cast<const uint16_t*>(as + k * (BM * 2) + pc * 16 + (row & 7) * 2);
+          row_sum += __uint_as_float(((uint32_t)bits) << 16);
+        }
+      }
+    }
+  }
+  if (want_row_sum && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = row_sum;
+  wait_loads_and_barrier<0>();  // every wave is done with the tile ring
+  float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (WN + 4));
+  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset(p.c_batch, z));
+}
+
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB, Gather GA, Gather GB>
+hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
+  GemmParams p = make_params(q, BM, BN);
+  int grid_y = q.batch;
+  if (q.k_splits > 1) {
+    const int tiles = (q.K + kTileK - 1) / kTileK;
+    p.k_tiles_per_split = (tiles + q.k_splits - 1) / q.k_splits;
+    p.c_batch.outer = (long long)q.M * q.ldc; p.c_batch.inner = 0; p.c_batch.inner_count = 1;
+    grid_y = q.k_splits;
+  }
+  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kRowBytes;
+  static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
+  auto kernel = gemm_bf16_dma_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, LA, LB, GA, GB>;
+  if (lds_bytes > 64 * 1024) {
+    static bool raised = false;  // per instantiation
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
+// Tile choice.  A 256 x 256 tile reads half as many operand bytes per flop from L2 as a 128 x 128 one, which is
+// what large products need; it only pays once there are enough tiles for two rounds over the 256 CUs.  A
+// dimension of 64 or less (a 64-channel convolution) gets a 64-wide tile so that no matrix-core work is spent
+// on rows that do not exist.  Small products take 64 x 64 tiles and a deeper ring: they are bound by latency.
+template <Layout LA, Layout LB, Gather GA = Gather::None, Gather GB = Gather::None>
+hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
+  auto tiles = [&](int tm, int tn) { return (long)((q.M + tm - 1) / tm) * ((q.N + tn - 1) / tn) * q.batch * q.k_splits; };
+  if (q.N <= 64 && q.M > 64) {
+    if (tiles(256, 64) >= 256) return launch_tile<256, 64, 3, 4, 1, LA, LB, GA, GB>(q, stream);
+    return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
+  }
+  if (q.M <= 64 && q.N > 64) {
+    if (tiles(64, 256) >= 256) return launch_tile<64, 256, 3, 1, 4, LA, LB, GA, GB>(q, stream);
+    return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
+  }
+  if (tiles(256, 256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
+  if (tiles(128, 128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
+  return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
+}
+
+}  // namespace gemm_dma_detail
+}  // namespace spb

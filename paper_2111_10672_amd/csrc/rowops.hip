@@ -170,15 +170,19 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const uint16_t* __re
   for (int col = threadIdx.x; col < 2 * width; col += 256) partial[(size_t)blockIdx.x * 2 * width + col] = sh[col];
 }
 
-// out_a[c] = sum_b partial[b][0][c];  out_b[c] = sum_b partial[b][1][c], blocks added in index order.
+// out_a[c] = sum_b partial[b][0][c];  out_b[c] = sum_b partial[b][1][c].  One wavefront per column: lane l adds blocks
+// l, l + 64, ... in order, then the lane sums are combined by a fixed shuffle tree (same bits on every run).
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int n_blocks, int width,
                                                               float* __restrict__ out_a, float* __restrict__ out_b) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
+  const int lane = threadIdx.x & 63, col = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (col >= 2 * width) return;
   float s = 0.f;
-  for (int b = 0; b < n_blocks; ++b) s += partial[(size_t)b * 2 * width + col];
-  if (col < width) out_a[col] = s;
-  else out_b[col - width] = s;
+  for (int b = lane; b < n_blocks; b += 64) s += partial[(size_t)b * 2 * width + col];
+  s = wave_sum(s);
+  if (lane == 0) {
+    if (col < width) out_a[col] = s;
+    else out_b[col - width] = s;
+  }
 }
 
 // p[r, :] = softmax(s[r, :]) in bfloat16; one wavefront per row.
@@ -311,7 +315,7 @@ hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx
                      partial, n_rows, width);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 255) / 256), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 3) / 4), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
   return hipGetLastError();
 }
 
