@@ -205,7 +205,7 @@ def main():
         "workspace_bytes_by_depth": {str(k): spb.spb_workspace_size(model.handle, k) for k in depths},
         "wall_ms_timed_region": round(wall_ms, 3),
         "roofline": roofline,
-        "kernels": table,
+        "kernels": sorted(table, key=lambda r: -r["avg_us"] * r["launches_per_sweep"])[:16],
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, params, batch, depths, args.cpu_seconds)

@@ -101,7 +101,7 @@ typedef struct spb_grad_view {
 
 /* Per-kernel timing record (see spb_set_kernel_timing). */
 typedef struct spb_kernel_time {
-  char name[SPB_NAME_LEN]; /* kernel class, e.g. "gemm_bf16_wgrad" */
+  char name[SPB_NAME_LEN]; /* kernel class; matrix products carry their shape: "gemm_bf16_wgrad 1024x1024x256" */
   int64_t launches;
   double total_ms; /* sum of HIP-event durations of those launches */
   double flops;    /* algorithmic floating-point operations of those launches (2*M*N*K per product) */
@@ -178,7 +178,7 @@ int spb_set_kernel_timing(spb_model* m, int32_t enable);
 int spb_read_kernel_timing(spb_model* m, spb_kernel_time* out, int32_t cap, int32_t* n_out);
 
 /* Measurement aid: enqueue `count` back-to-back copies of the most recent matrix product of kernel class
- * `name` (e.g. "gemm_bf16_fwd") that ran while timing was enabled, on the same operands (the workspace of the
+ * `name` (as spb_read_kernel_timing reports it, e.g. "gemm_bf16_fwd 256x1024x1024") that ran while timing was enabled, on the same operands (the workspace of the
  * last step must still be alive; the copies rewrite that product's output with the same values).  Two events
  * around the call give the kernel's duration without the per-launch event overhead.
  * Errors: INVALID_ARG, STATE (no such product recorded), HIP. */

@@ -207,7 +207,7 @@ def spb_replay_kernel(m, name: str, count: int, stream):
     _check(lib().spb_replay_kernel(m, name.encode(), count, C.c_void_p(stream)))
 
 
-def spb_read_kernel_timing(m, cap=64):
+def spb_read_kernel_timing(m, cap=1024):
     recs = (spb_kernel_time * cap)()
     n = C.c_int32()
     _check(lib().spb_read_kernel_timing(m, recs, cap, C.byref(n)))

@@ -33,8 +33,13 @@ int Model::replay(const char* name, int count, hipStream_t s) {
 }
 
 int Model::gemm(const GemmProblem& p, hipStream_t s) {
-  if (timer.enabled()) last_product[p.name] = p;
-  hipError_t e = timer.run(p.name, gemm_flops(p), gemm_bytes(p), s, [&] { return launch_gemm(p, s); });
+  if (!timer.enabled()) return check(launch_gemm(p, s), p.name);
+  // while timing, products are told apart by shape as well: "conv_fwd 200704x256x64"
+  char key[SPB_NAME_LEN];
+  if (p.batch > 1) std::snprintf(key, sizeof key, "%s %dx%dx%d b%d", p.name, p.M, p.N, p.K, p.batch);
+  else std::snprintf(key, sizeof key, "%s %dx%dx%d", p.name, p.M, p.N, p.K);
+  last_product[key] = p;
+  hipError_t e = timer.run(key, gemm_flops(p), gemm_bytes(p), s, [&] { return launch_gemm(p, s); });
   return check(e, p.name);
 }
 

@@ -210,114 +210,175 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // Epilogue.  Each wave parks 32 rows of its WM x WN accumulator tile at a time in its own LDS region (the tile
 // ring is dead by then) and reads them back row by row, so that bias, mask and result move in 16-byte pieces
 // along n.  LDS operations of one wave complete in order, so the pieces need no barrier between them.
+// The row loops are deliberately not unrolled: an unrolled epilogue is tens of thousands of instructions,
+// which no longer fit the instruction cache and cost more time than the tile loop itself.
+
+// All bfloat16 epilogues are one formula per element,
+//     out = act(alpha * acc * s + b + r),
+// with s, b per column and r per element:  BiasAct: s = column scale or 1, b = bias or 0, r = residual or 0;
+// MaskStore: s = [x > 0]; GeluBwdStore: s = gelu'(x), where x is the per-element tensor `mask`.  At most one
+// per-element tensor is read (residual or mask), so a unit of 8 outputs costs one optional 16-byte global load,
+// which is fetched one unit ahead of its use.
+
+__device__ __forceinline__ void unpack_bf16x8(const u32x4& w, float (&f)[8]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
+}
+__device__ __forceinline__ u32x4 pack_bf16x8(const float (&f)[8]) {
+  u32x4 o;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) o[d] = pack_bf16(f[2 * d], f[2 * d + 1]);
+  return o;
+}
+
+// ragged right edge: the last, partly filled group of columns, element by element, straight from the parked row
+__device__ __forceinline__ void store_ragged(const GemmParams& p, const float* parked, int count, int m, int n, long long c_offset) {
+  const bf16_t* bias = static_cast<const bf16_t*>(p.bias);
+  if (p.epilogue == (int)Epilogue::StoreF32) {
+    float* dst = static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n;
+#pragma unroll 1
+    for (int e = 0; e < count && n + e < p.N; ++e) dst[e] = parked[e] * p.alpha + (bias ? to_float(bias[n + e]) : 0.f);
+    return;
+  }
+  const bf16_t* mask = static_cast<const bf16_t*>(p.mask);
+  const bf16_t* res = static_cast<const bf16_t*>(p.residual);
+  const bf16_t* cscale = static_cast<const bf16_t*>(p.col_scale);
+  bf16_t* aux = static_cast<bf16_t*>(p.aux_out);
+  bf16_t* dst = static_cast<bf16_t*>(p.C) + c_offset + (size_t)m * p.ldc + n;
+#pragma unroll 1
+  for (int e = 0; e < count && n + e < p.N; ++e) {
+    float v = parked[e] * p.alpha, pre = v;
+    if (p.epilogue == (int)Epilogue::MaskStore) v = to_float(mask[(size_t)m * p.ldmask + n + e]) > 0.f ? v : 0.f;
+    else if (p.epilogue == (int)Epilogue::GeluBwdStore) v *= gelu_grad_f(to_float(mask[(size_t)m * p.ldmask + n + e]));
+    else {
+      v = v * (cscale ? to_float(cscale[n + e]) : 1.f) + (bias ? to_float(bias[n + e]) : 0.f);
+      if (!p.aux_raw) pre = v;
+      if (res) v += to_float(res[(size_t)m * p.ldres + n + e]);
+      if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
+      else if (p.act == (int)Act::Gelu) v = gelu_f(v);
+      if (aux) store_elem(aux + (size_t)m * p.ldaux + n + e, pre);
+    }
+    store_elem(dst + e, v);
+  }
+}
+
+template <int WN>
+__device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset) {
+  constexpr int kPitch = WN + 4;
+  constexpr int kPerRow = WN / 4;             // 4-column units per row; 64 % kPerRow == 0, so a lane's column never changes
+  const int c = (lane % kPerRow) * 4, n = col_base + c;
+  if (n >= p.N) return;
+  const bool whole = n + 4 <= p.N;
+  f32x4 b = {0.f, 0.f, 0.f, 0.f};
+  if (p.bias && whole) {
+    const uint2 bb = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(p.bias) + n);
+    b[0] = __uint_as_float(bb.x << 16); b[1] = __uint_as_float(bb.x & 0xFFFF0000u);
+    b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xFFFF0000u);
+  }
+#pragma unroll 1
+  for (int row = lane / kPerRow; row < 32; row += 64 / kPerRow) {
+    const int m = piece_row + row;
+    if (m >= p.M) break;
+    if (whole) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c) * p.alpha + b;
+      *reinterpret_cast<f32x4*>(static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n) = v;
+    } else {
+      store_ragged(p, stage + row * kPitch + c, 4, m, n, c_offset);
+    }
+  }
+}
+
+template <int WN>
+__device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset) {
+  constexpr int kPitch = WN + 4;
+  constexpr int kPerRow = WN / 8;             // 8-column units per row; a lane's column never changes
+  constexpr int kRowStep = 64 / kPerRow;
+  const int c = (lane % kPerRow) * 8, n = col_base + c;
+  if (n >= p.N) return;
+  const int mode = p.epilogue;
+  const bool plain = mode == (int)Epilogue::BiasAct;
+  bf16_t* aux = plain ? static_cast<bf16_t*>(p.aux_out) : nullptr;
+  // the per-element tensor this epilogue reads, if any
+  const bf16_t* xsrc = plain ? static_cast<const bf16_t*>(p.residual) : static_cast<const bf16_t*>(p.mask);
+  const int ldx = plain ? p.ldres : p.ldmask;
+  if (n + 8 > p.N) {
+#pragma unroll 1
+    for (int row = lane / kPerRow; row < 32 && piece_row + row < p.M; row += kRowStep)
+      store_ragged(p, stage + row * kPitch + c, 8, piece_row + row, n, c_offset);
+    return;
+  }
+  float sc[8], bs[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { sc[e] = 1.f; bs[e] = 0.f; }
+  if (plain && p.col_scale) unpack_bf16x8(*reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.col_scale) + n), sc);
+  if (plain && p.bias) unpack_bf16x8(*reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.bias) + n), bs);
+  // One unit: 8 outputs of row `row` from the parked accumulators and the per-element tensor's chunk xcur.
+  auto unit = [&](int row, int m, const u32x4& xcur) {
+    float v[8], x[8], pre[8];
+    const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
+    const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+    unpack_bf16x8(xcur, x);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = v0[e] * p.alpha; v[4 + e] = v1[e] * p.alpha; }
+    if (mode == (int)Epilogue::MaskStore) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = x[e] > 0.f ? v[e] : 0.f;
+    } else if (mode == (int)Epilogue::GeluBwdStore) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(x[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        pre[e] = v[e];
+        v[e] = v[e] * sc[e] + bs[e];
+        if (!p.aux_raw) pre[e] = v[e];
+        v[e] += x[e];                           // a residual joins before the activation (residual blocks); x = 0 without one
+      }
+      if (p.act == (int)Act::Relu) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+      } else if (p.act == (int)Act::Gelu) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+      }
+      if (aux) *reinterpret_cast<u32x4*>(aux + (size_t)m * p.ldaux + n) = pack_bf16x8(pre);
+    }
+    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.C) + c_offset + (size_t)m * p.ldc + n) = pack_bf16x8(v);
+  };
+  const int row0 = lane / kPerRow;
+  if (xsrc == nullptr) {   // nothing to read per element: stores only, nothing to wait for
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll 1
+    for (int row = row0; row < 32 && piece_row + row < p.M; row += kRowStep) unit(row, piece_row + row, zero);
+    return;
+  }
+  // The tensor's chunk for the next unit is requested (from a clamped, always valid row) before this unit's
+  // stores are issued, so waiting for it never waits for a store.
+  const int last_row = p.M - 1;
+  u32x4 xnext = *reinterpret_cast<const u32x4*>(xsrc + (size_t)min(piece_row + row0, last_row) * ldx + n);
+#pragma unroll 1
+  for (int row = row0; row < 32 && piece_row + row < p.M; row += kRowStep) {
+    const int m = piece_row + row;
+    const u32x4 xcur = xnext;
+    xnext = *reinterpret_cast<const u32x4*>(xsrc + (size_t)min(m + kRowStep, last_row) * ldx + n);
+    unit(row, m, xcur);
+  }
+}
+
 template <int WM, int WN>
 __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage,
                                                 int row_base, int col_base, int lane, long long c_offset) {
   constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of rows 4 apart
-  const bf16_t* bias = static_cast<const bf16_t*>(p.bias);
 #pragma unroll
   for (int piece = 0; piece < WM / 32; ++piece) {
-  const int piece_row = row_base + piece * 32;
 #pragma unroll
-  for (int j = 0; j < WN / 32; ++j)
+    for (int j = 0; j < WN / 32; ++j)
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-      stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[piece][j][r];
-  if (p.epilogue == (int)Epilogue::StoreF32) {
-    constexpr int kUnits = 32 * WN / 4;
-#pragma unroll
-    for (int it = 0; it < kUnits / 64; ++it) {
-      const int u = it * 64 + lane;
-      const int row = u / (WN / 4), c = (u % (WN / 4)) * 4;
-      const int m = piece_row + row, n = col_base + c;
-      if (m >= p.M || n >= p.N) continue;
-      f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c) * p.alpha;
-      float* dst = static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n;
-      if (n + 4 <= p.N) {
-        if (bias) {
-          const uint2 bb = *reinterpret_cast<const uint2*>(bias + n);
-          v[0] += __uint_as_float(bb.x << 16); v[1] += __uint_as_float(bb.x & 0xFFFF0000u);
-          v[2] += __uint_as_float(bb.y << 16); v[3] += __uint_as_float(bb.y & 0xFFFF0000u);
-        }
-        *reinterpret_cast<f32x4*>(dst) = v;
-      } else {
-        for (int e = 0; e < 4 && n + e < p.N; ++e) dst[e] = v[e] + (bias ? to_float(bias[n + e]) : 0.f);
-      }
-    }
-  } else {
-    constexpr int kUnits = 32 * WN / 8;
-    const int mode = p.epilogue;  // BiasAct, MaskStore or GeluBwdStore
-    const bf16_t* mask = static_cast<const bf16_t*>(p.mask);
-    const bf16_t* res = static_cast<const bf16_t*>(p.residual);
-    bf16_t* aux = static_cast<bf16_t*>(p.aux_out);
-    auto unpack = [](const u32x4& w, float (&f)[8]) {
-#pragma unroll
-      for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
-    };
-    auto pack = [](const float (&f)[8]) {
-      u32x4 o;
-#pragma unroll
-      for (int d = 0; d < 4; ++d) o[d] = pack_bf16(f[2 * d], f[2 * d + 1]);
-      return o;
-    };
-    // one element of the epilogue, shared by the 16-byte path and the ragged tail
-    const bf16_t* cscale = static_cast<const bf16_t*>(p.col_scale);
-    // (in BiasAct mode mk carries the column scale, 1 if there is none)
-    auto finish = [&](float v, float b, float mk, float r, float& pre) {
-      if (mode == (int)Epilogue::MaskStore) return mk > 0.f ? v : 0.f;
-      if (mode == (int)Epilogue::GeluBwdStore) return v * gelu_grad_f(mk);
-      v *= p.alpha;
-      pre = v;
-      v = v * mk + b;
-      if (!p.aux_raw) pre = v;
-      v += r;                                   // a residual joins before the activation (residual blocks)
-      if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
-      else if (p.act == (int)Act::Gelu) v = gelu_f(v);
-      return v;
-    };
-#pragma unroll
-    for (int it = 0; it < kUnits / 64; ++it) {
-      const int u = it * 64 + lane;
-      const int row = u / (WN / 8), c = (u % (WN / 8)) * 8;
-      const int m = piece_row + row, n = col_base + c;
-      if (m >= p.M || n >= p.N) continue;
-      float v[8], b[8], mk[8], r[8], pre[8];
-      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
-      const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { b[e] = 0.f; mk[e] = 0.f; r[e] = 0.f; pre[e] = 0.f; }
-      bf16_t* dst = static_cast<bf16_t*>(p.C) + c_offset + (size_t)m * p.ldc + n;
-      if (n + 8 <= p.N) {
-        if (mode != (int)Epilogue::BiasAct) {
-          unpack(*reinterpret_cast<const u32x4*>(mask + (size_t)m * p.ldmask + n), mk);
-        } else {
-          if (cscale) unpack(*reinterpret_cast<const u32x4*>(cscale + n), mk);
-          else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) mk[e] = 1.f;
-          }
-          if (bias) unpack(*reinterpret_cast<const u32x4*>(bias + n), b);
-          if (res) unpack(*reinterpret_cast<const u32x4*>(res + (size_t)m * p.ldres + n), r);
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = finish(v[e], b[e], mk[e], r[e], pre[e]);
-        if (aux && mode == (int)Epilogue::BiasAct) *reinterpret_cast<u32x4*>(aux + (size_t)m * p.ldaux + n) = pack(pre);
-        *reinterpret_cast<u32x4*>(dst) = pack(v);
-      } else {
-        for (int e = 0; e < 8 && n + e < p.N; ++e) {
-          float be = 0.f, me = 0.f, re = 0.f, pe = 0.f;
-          if (mode != (int)Epilogue::BiasAct) me = to_float(mask[(size_t)m * p.ldmask + n + e]);
-          else { me = cscale ? to_float(cscale[n + e]) : 1.f; if (bias) be = to_float(bias[n + e]); if (res) re = to_float(res[(size_t)m * p.ldres + n + e]); }
-          const float x = finish(v[e], be, me, re, pe);
-          if (aux && mode == (int)Epilogue::BiasAct) store_elem(aux + (size_t)m * p.ldaux + n + e, pe);
-          store_elem(dst + e, x);
-        }
-      }
-    }
+      for (int r = 0; r < 16; ++r)
+        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[piece][j][r];
+    if (p.epilogue == (int)Epilogue::StoreF32) store_rows_f32<WN>(p, stage, row_base + piece * 32, col_base, lane, c_offset);
+    else store_rows_bf16<WN>(p, stage, row_base + piece * 32, col_base, lane, c_offset);
   }
-  }  // piece
 }
 
 template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB, Gather GA, Gather GB>
