@@ -40,6 +40,24 @@ def parse():
     return ap.parse_args()
 
 
+def measured_traffic(kernel_name):
+    """HBM bytes per launch of the roofline kernel from the stored counter readings (FETCH_SIZE and WRITE_SIZE,
+    scaled by a plain copy's readings), or None when there are none for this kernel or the kernel's sources have
+    changed since they were taken."""
+    import hashlib
+    pkg = os.path.join(ROOT, "paper_2111_10672_amd")
+    try:
+        rec = json.load(open(os.path.join(pkg, "measured_traffic.json")))
+        h = hashlib.sha256()
+        for fn in rec["sources"]:
+            h.update(open(os.path.join(pkg, "csrc", fn), "rb").read())
+    except (OSError, KeyError, ValueError):
+        return None
+    if rec.get("kernel") != kernel_name or rec.get("sources_sha256") != h.hexdigest():
+        return None
+    return rec
+
+
 def cpu_baseline(cfg, params, batch, depths, budget_s):
     """The oracle as it stands, exact float64 mode, on this host's cores, on a bounded sample."""
     import oracle
@@ -181,8 +199,14 @@ def main():
         # note: the replayed product is the class's most recent launch; its flops are taken from that class's mean
         flops_per_launch = dom["flops"] / dom["launches"]
         achieved = flops_per_launch / back_to_back_us / 1e6       # TFLOP/s
+        rec = measured_traffic(dom["name"]) if args.config == "cfg2" else None
         roofline = {"kernel": dom["name"], "bound": "mfma", "achieved": round(achieved, 3), "peak": mfma_peak,
-                    "unit": "TFLOP/s", "frac": round(achieved / mfma_peak, 5), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(achieved / mfma_peak, 5),
+                    "traffic": rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"] if rec else None,
+                    "traffic_unit": "HBM bytes per launch (fetch + write)",
+                    "traffic_fetch": rec["fetch_bytes_per_launch"] if rec else None,
+                    "traffic_write": rec["write_bytes_per_launch"] if rec else None,
+                    "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"],
                     "avg_launch_us": round(back_to_back_us, 3),
                     "avg_launch_us_event_bracketed": round(dom["total_ms"] / dom["launches"] * 1e3, 3),
                     "flops_per_launch": flops_per_launch,

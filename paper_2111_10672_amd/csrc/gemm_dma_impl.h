@@ -23,6 +23,8 @@ namespace spb {
 namespace gemm_dma_detail {
 using namespace gemm_detail;
 
+__device__ __forceinline__ long long batch_offset_z(const BatchStride& b, int z) { return z == 0 ? 0 : batch_offset(b, z); }
+
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* global_ptr_t;
@@ -263,7 +265,7 @@ __device__ __forceinline__ void store_ragged(const GemmParams& p, const float* p
 }
 
 template <int WN>
-__device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset) {
+__device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset, int rows = 32) {
   constexpr int kPitch = WN + 4;
   constexpr int kPerRow = WN / 4;             // 4-column units per row; 64 % kPerRow == 0, so a lane's column never changes
   const int c = (lane % kPerRow) * 4, n = col_base + c;
@@ -276,7 +278,7 @@ __device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float*
     b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xFFFF0000u);
   }
 #pragma unroll 1
-  for (int row = lane / kPerRow; row < 32; row += 64 / kPerRow) {
+  for (int row = lane / kPerRow; row < rows; row += 64 / kPerRow) {
     const int m = piece_row + row;
     if (m >= p.M) break;
     if (whole) {
@@ -289,7 +291,7 @@ __device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float*
 }
 
 template <int WN>
-__device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset) {
+__device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset, int rows = 32) {
   constexpr int kPitch = WN + 4;
   constexpr int kPerRow = WN / 8;             // 8-column units per row; a lane's column never changes
   constexpr int kRowStep = 64 / kPerRow;
@@ -303,7 +305,7 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
   const int ldx = plain ? p.ldres : p.ldmask;
   if (n + 8 > p.N) {
 #pragma unroll 1
-    for (int row = lane / kPerRow; row < 32 && piece_row + row < p.M; row += kRowStep)
+    for (int row = lane / kPerRow; row < rows && piece_row + row < p.M; row += kRowStep)
       store_ragged(p, stage + row * kPitch + c, 8, piece_row + row, n, c_offset);
     return;
   }
@@ -349,7 +351,7 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
   if (xsrc == nullptr) {   // nothing to read per element: stores only, nothing to wait for
     const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll 1
-    for (int row = row0; row < 32 && piece_row + row < p.M; row += kRowStep) unit(row, piece_row + row, zero);
+    for (int row = row0; row < rows && piece_row + row < p.M; row += kRowStep) unit(row, piece_row + row, zero);
     return;
   }
   // The tensor's chunk for the next unit is requested (from a clamped, always valid row) before this unit's
@@ -357,7 +359,7 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
   const int last_row = p.M - 1;
   u32x4 xnext = *reinterpret_cast<const u32x4*>(xsrc + (size_t)min(piece_row + row0, last_row) * ldx + n);
 #pragma unroll 1
-  for (int row = row0; row < 32 && piece_row + row < p.M; row += kRowStep) {
+  for (int row = row0; row < rows && piece_row + row < p.M; row += kRowStep) {
     const int m = piece_row + row;
     const u32x4 xcur = xnext;
     xnext = *reinterpret_cast<const u32x4*>(xsrc + (size_t)min(m + kRowStep, last_row) * ldx + n);
@@ -410,8 +412,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     t_first = z * p.k_tiles_per_split;
     n_steps = min(n_steps, t_first + p.k_tiles_per_split);
   }
-  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset(p.a_batch, z), p.lda, m0, p.M, wave, lane, t_first, p.conv);
-  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset(p.b_batch, z), p.ldb, n0, p.N, wave, lane, t_first, p.conv);
+  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset_z(p.a_batch, z), p.lda, m0, p.M, wave, lane, t_first, p.conv);
+  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset_z(p.b_batch, z), p.ldb, n0, p.N, wave, lane, t_first, p.conv);
   auto issue = [&](int t) {
     char* stage = lds + ((t - t_first) % STAGES) * kStageBytes;
     src_a.issue(t, p.K, stage, wave, p.lda, p.conv);
@@ -429,8 +431,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Bias gradient of a weight-gradient product: sum over k of A(row, k).  A KRow tile has 8 consecutive rows in
+  // one 16-byte chunk, so a thread takes one chunk column and every kPhases-th k-row, keeps 8 partial sums and
+  // the partial sums of the kPhases threads of a chunk are added up once, after the tile loop.
+  constexpr int kChunks = BM / 8, kPhases = 64 * NW / kChunks;
+  static_assert(kPhases >= 1 && kTileK % kPhases == 0 && (size_t)kPhases * BM * 4 <= (size_t)STAGES * kStageBytes, "row-sum partition");
   const bool want_row_sum = LA == Layout::KRow && p.a_row_sum != nullptr && tile_n == 0;
-  float row_sum = 0.f;
+  float row_sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int sum_chunk = threadIdx.x % kChunks, sum_phase = threadIdx.x / kChunks;
 
   for (int t = t_first; t < n_steps; ++t) {
     // Tiles t+1 .. t+STAGES-2 may stay in flight if they were all issued; near the end wait for everything.
@@ -466,21 +474,200 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
       }
     }
     if constexpr (LA == Layout::KRow) {
-      if (want_row_sum && threadIdx.x < BM) {  // bias gradient: sum over k of A(row, k), tile rows lie along the LDS row
-        const int row = threadIdx.x;
-#pragma unroll 8
-        for (int k = 0; k < kTileK; ++k) {
-          const int pc = ((row >> 3) + krow_rot<BM>(k)) & (BM / 8 - 1);
-          const uint16_t bits = *reinterpret_cast<const uint16_t*>(as + k * (BM * 2) + pc * 16 + (row & 7) * 2);
-          row_sum += __uint_as_float(((uint32_t)bits) << 16);
+      if (want_row_sum) {
+#pragma unroll
+        for (int j = 0; j < kTileK / kPhases; ++j) {
+          const int k = sum_phase + j * kPhases;
+          const int pc = (sum_chunk + krow_rot<BM>(k)) & (kChunks - 1);
+          float f[8];
+          unpack_bf16x8(*reinterpret_cast<const u32x4*>(as + k * (BM * 2) + pc * 16), f);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) row_sum[e] += f[e];
         }
       }
     }
   }
-  if (want_row_sum && threadIdx.x < BM && m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = row_sum;
   wait_loads_and_barrier<0>();  // every wave is done with the tile ring
+  if constexpr (LA == Layout::KRow) {
+    if (want_row_sum) {  // uniform over the workgroup
+      float* part = reinterpret_cast<float*>(lds);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part[sum_phase * BM + sum_chunk * 8 + e] = row_sum[e];
+      __syncthreads();
+      if (threadIdx.x < BM) {
+        float v = 0.f;
+#pragma unroll
+        for (int ph = 0; ph < kPhases; ++ph) v += part[ph * BM + threadIdx.x];
+        if (m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = v;
+      }
+      __syncthreads();
+    }
+  }
   float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (WN + 4));
-  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset(p.c_batch, z));
+  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z));
+}
+
+// Small products (at most a few workgroups per CU) are a chain of latencies, not a throughput problem, and the
+// one throughput that does bound them is a CU's vector-memory path of about 57 bytes per clock.  So: tiles small
+// enough that every CU gets one (32 x 32 or 64 x 64), and no barrier in the tile loop at all: each of the four
+// waves owns a contiguous quarter of the k range with a tile ring of its own in LDS, waits only on its own
+// loads, and drifts freely against the others, which overlaps one wave's loads with another's LDS reads and
+// MFMAs.  The four partial tiles are summed through LDS at the end, each wave finishing a quarter of the rows.
+template <int VM>
+__device__ __forceinline__ void wait_own_loads() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(waitcnt_imm(VM, 15));
+  asm volatile("" ::: "memory");
+}
+
+template <int BM, int BN, Layout LA, Layout LB>
+__global__ __launch_bounds__(256) void gemm_bf16_small_kernel(GemmParams p) {
+  constexpr int NW = 4, TM = BM / 32, TN = BN / 32;
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  constexpr int SW = (BM + BN) <= 64 ? 4 : 2;   // ring depth per wave; four rings fill 128 KiB
+  constexpr int kLoads = (BM + BN) / 8;        // direct-to-LDS instructions per tile (one wave loads a whole tile)
+  constexpr int kPitch = BN + 4;               // floats per parked row; column BN carries the row sum of A
+  constexpr int kRows = BM / NW;               // rows each wave finishes
+  static_assert((BM == 32 || BM == 64) && (BN == 32 || BN == 64), "small tiles");
+  static_assert((size_t)NW * BM * kPitch * 4 <= (size_t)NW * SW * kStageBytes, "the four partial tiles fit in the rings");
+  static_assert(SW * kLoads < 64, "vmcnt range");
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
+  const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* ring = lds + wave * (SW * kStageBytes);
+
+  const int z = blockIdx.y;  // batch entry, or slice of the k range
+  int t_first = 0, t_end = (p.K + kTileK - 1) / kTileK;
+  if (p.k_tiles_per_split > 0) {
+    t_first = z * p.k_tiles_per_split;
+    t_end = min(t_end, t_first + p.k_tiles_per_split);
+  }
+  const int per_wave = (max(t_end - t_first, 0) + NW - 1) / NW;
+  const int my_first = t_first + wave * per_wave;
+  const int n = max(min(t_end, my_first + per_wave) - my_first, 0);  // tiles of this wave
+
+  TileSource<BM, LA, Gather::None, 1> src_a;
+  TileSource<BN, LB, Gather::None, 1> src_b;
+  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset_z(p.a_batch, z), p.lda, m0, p.M, 0, lane, my_first, p.conv);
+  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset_z(p.b_batch, z), p.ldb, n0, p.N, 0, lane, my_first, p.conv);
+  auto issue = [&](int i) {  // i-th tile of this wave, into its ring slot i % SW
+    char* stage = ring + (i % SW) * kStageBytes;
+    src_a.issue(my_first + i, p.K, stage, 0, p.lda, p.conv);
+    src_b.issue(my_first + i, p.K, stage + BM * kRowBytes, 0, p.ldb, p.conv);
+  };
+#pragma unroll
+  for (int s = 0; s < SW; ++s)
+    if (s < n) issue(s);
+
+  f32x16 acc[TM][TN], acc_sum[TM];
+#pragma unroll
+  for (int x = 0; x < TM; ++x) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      acc_sum[x][r] = 0.f;
+#pragma unroll
+      for (int y = 0; y < TN; ++y) acc[x][y][r] = 0.f;
+    }
+  }
+  // bias gradient of a weight-gradient product: row sums of A, as one more MFMA against a fragment of ones
+  const bool want_row_sum = p.a_row_sum != nullptr && tile_n == 0;
+  const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+
+  for (int i = 0; i < n; ++i) {
+    // tile i has landed once only the tiles issued after it are still in flight
+    const int younger = min(SW - 1, n - 1 - i);
+    if (younger == SW - 1) wait_own_loads<(SW - 1) * kLoads>();
+    else if (SW > 2 && younger == 2) wait_own_loads<2 * kLoads>();
+    else if (SW > 2 && younger == 1) wait_own_loads<1 * kLoads>();
+    else wait_own_loads<0>();
+    const char* as = ring + (i % SW) * kStageBytes;
+    const char* bs = as + BM * kRowBytes;
+    u32x4 a[4 * TM], b[4 * TN];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+#pragma unroll
+      for (int x = 0; x < TM; ++x) a[g * TM + x] = read_fragment<BM, LA>(as, x * 32, g, lane);
+#pragma unroll
+      for (int y = 0; y < TN; ++y) b[g * TN + y] = read_fragment<BN, LB>(bs, y * 32, g, lane);
+    }
+    fragments_ready(a, b);  // the slot is free again
+    if (i + SW < n) issue(i + SW);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+#pragma unroll
+      for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int y = 0; y < TN; ++y)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[g * TM + x]), __builtin_bit_cast(bf16x8, b[g * TN + y]), acc[x][y], 0, 0, 0);
+      if (want_row_sum) {
+#pragma unroll
+        for (int x = 0; x < TM; ++x)
+          acc_sum[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[g * TM + x]), __builtin_bit_cast(bf16x8, ones), acc_sum[x], 0, 0, 0);
+      }
+    }
+  }
+  wait_loads_and_barrier<0>();  // every wave is done with its ring: park the partial tiles there
+
+  float* red = reinterpret_cast<float*>(lds);
+  float* mine = red + wave * (BM * kPitch);
+#pragma unroll
+  for (int x = 0; x < TM; ++x) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = 32 * x + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+#pragma unroll
+      for (int y = 0; y < TN; ++y) mine[row * kPitch + 32 * y + (lane & 31)] = acc[x][y][r];
+      if (want_row_sum && (lane & 31) == 0) mine[row * kPitch + BN] = acc_sum[x][r];
+    }
+  }
+  __syncthreads();
+  // wave w finishes rows kRows * w ..: sum of the four partials, in place in the first one
+  const int row_base = kRows * wave;
+  constexpr int kUnits = kRows * (BN / 4) / 64;  // 16-byte units per lane
+  static_assert(kUnits >= 1, "a wave's rows fill its lanes");
+#pragma unroll
+  for (int q = 0; q < kUnits; ++q) {
+    const int idx = q * 64 + lane;
+    float* at = red + (row_base + idx / (BN / 4)) * kPitch + (idx % (BN / 4)) * 4;
+    f32x4 v = *reinterpret_cast<const f32x4*>(at);
+#pragma unroll
+    for (int w = 1; w < NW; ++w) v += *reinterpret_cast<const f32x4*>(at + w * (BM * kPitch));
+    *reinterpret_cast<f32x4*>(at) = v;
+  }
+  if (want_row_sum && lane < kRows) {
+    const float* at = red + (row_base + lane) * kPitch + BN;
+    const float v = at[0] + at[BM * kPitch] + at[2 * BM * kPitch] + at[3 * BM * kPitch];
+    if (m0 + row_base + lane < p.M) p.a_row_sum[m0 + row_base + lane] = v;
+  }
+  const float* stage = red + row_base * kPitch;
+  if (p.epilogue == (int)Epilogue::StoreF32) store_rows_f32<BN>(p, stage, m0 + row_base, n0, lane, batch_offset_z(p.c_batch, z), kRows);
+  else store_rows_bf16<BN>(p, stage, m0 + row_base, n0, lane, batch_offset_z(p.c_batch, z), kRows);
+}
+
+template <int BM, int BN, Layout LA, Layout LB>
+hipError_t launch_small(const GemmProblem& q, hipStream_t stream) {
+  GemmParams p = make_params(q, BM, BN);
+  int grid_y = q.batch;
+  if (q.k_splits > 1) {
+    const int tiles = (q.K + kTileK - 1) / kTileK;
+    p.k_tiles_per_split = (tiles + q.k_splits - 1) / q.k_splits;
+    p.c_batch.outer = (long long)q.M * q.ldc; p.c_batch.inner = 0; p.c_batch.inner_count = 1;
+    grid_y = q.k_splits;
+  }
+  constexpr size_t lds_bytes = 128 * 1024;
+  auto kernel = gemm_bf16_small_kernel<BM, BN, LA, LB>;
+  static bool raised = false;  // per instantiation
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(256), lds_bytes, stream, p);
+  return hipGetLastError();
 }
 
 template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, Layout LA, Layout LB, Gather GA, Gather GB>
@@ -525,6 +712,10 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   }
   if (tiles(256, 256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
   if (tiles(128, 128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
+  if constexpr (GA == Gather::None && GB == Gather::None) {
+    if (tiles(64, 64) >= 192) return launch_small<64, 64, LA, LB>(q, stream);
+    return launch_small<32, 32, LA, LB>(q, stream);
+  }
   return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
 }
 
