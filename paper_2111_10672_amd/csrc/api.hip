@@ -27,8 +27,9 @@ int Model::check(hipError_t e, const char* what) {
 int Model::replay(const char* name, int count, hipStream_t s) {
   auto it = last_product.find(name);
   if (it == last_product.end()) { set_error("spb_replay_kernel: no product of class %s has run with timing enabled", name); return SPB_ERR_STATE; }
+  const Product& pr = it->second;
   for (int i = 0; i < count; ++i)
-    if (int rc = check(launch_gemm(it->second, s), name)) return rc;
+    if (int rc = check(pr.pair ? launch_gemm_pair(pr.first, pr.second, s) : launch_gemm(pr.first, s), name)) return rc;
   return SPB_OK;
 }
 
@@ -38,9 +39,26 @@ int Model::gemm(const GemmProblem& p, hipStream_t s) {
   char key[SPB_NAME_LEN];
   if (p.batch > 1) std::snprintf(key, sizeof key, "%s %dx%dx%d b%d", p.name, p.M, p.N, p.K, p.batch);
   else std::snprintf(key, sizeof key, "%s %dx%dx%d", p.name, p.M, p.N, p.K);
-  last_product[key] = p;
+  Product pr;
+  pr.first = p;
+  last_product[key] = pr;
   hipError_t e = timer.run(key, gemm_flops(p), gemm_bytes(p), s, [&] { return launch_gemm(p, s); });
   return check(e, p.name);
+}
+
+int Model::gemm_pair(const GemmProblem& d, const GemmProblem& w, hipStream_t s) {
+  if (!gemm_pair_shares_launch(d, w)) {
+    if (int rc = gemm(w, s)) return rc;
+    return gemm(d, s);
+  }
+  if (!timer.enabled()) return check(launch_gemm_pair(d, w, s), d.name);
+  char key[SPB_NAME_LEN];
+  std::snprintf(key, sizeof key, "%s+w %dx%dx%d+%dx%dx%d", d.name, d.M, d.N, d.K, w.M, w.N, w.K);
+  Product pr;
+  pr.first = d; pr.second = w; pr.pair = true;
+  last_product[key] = pr;
+  hipError_t e = timer.run(key, gemm_flops(d) + gemm_flops(w), gemm_bytes(d) + gemm_bytes(w), s, [&] { return launch_gemm_pair(d, w, s); });
+  return check(e, d.name);
 }
 
 int Model::run(const char* name, double bytes, hipStream_t s, const std::function<hipError_t()>& launch) {

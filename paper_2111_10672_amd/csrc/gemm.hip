@@ -295,25 +295,45 @@ double gemm_bytes(const GemmProblem& p) {
   return b * p.batch;
 }
 
-hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream) {
+namespace {
+// what every product must satisfy, whichever kernel takes it
+bool operands_valid(const GemmProblem& p) {
   const int per = p.dtype == DType::F32 ? 4 : 8;  // elements per 16-byte chunk
-  if (p.M <= 0 || p.N <= 0 || p.K <= 0 || !p.A || !p.B || !p.C) return hipErrorInvalidValue;
-  if (!aligned16(p.A) || !aligned16(p.B)) return hipErrorInvalidValue;
+  if (p.M <= 0 || p.N <= 0 || p.K <= 0 || !p.A || !p.B || !p.C) return false;
+  if (!aligned16(p.A) || !aligned16(p.B)) return false;
   // Vector loads: the contiguous extent of each operand must be whole 16-byte chunks inside its pitch.
-  if (p.lda % per || p.ldb % per) return hipErrorInvalidValue;
+  if (p.lda % per || p.ldb % per) return false;
   auto extent_ok = [&](Layout l, int rows, int ld) {
     const int extent = l == Layout::RowK ? p.K : rows;
     return (extent + per - 1) / per * per <= ld;
   };
-  if (!extent_ok(p.a_layout, p.M, p.lda) || !extent_ok(p.b_layout, p.N, p.ldb)) return hipErrorInvalidValue;
-  if (p.ldc < p.N) return hipErrorInvalidValue;
-  if (p.epilogue == Epilogue::MaskStore && (!p.mask || p.ldmask < p.N)) return hipErrorInvalidValue;
+  if (!extent_ok(p.a_layout, p.M, p.lda) || !extent_ok(p.b_layout, p.N, p.ldb)) return false;
+  if (p.ldc < p.N) return false;
+  if (p.epilogue == Epilogue::MaskStore && (!p.mask || p.ldmask < p.N)) return false;
+  return true;
+}
+}  // namespace
+
+hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream) {
+  if (!operands_valid(p)) return hipErrorInvalidValue;
   if (p.dtype == DType::BF16 && gemm_dma_accepts(p)) return launch_gemm_dma(p, stream);
   // the register-staged kernel below knows only the dense-layer epilogues of a single product
   if (p.batch != 1 || p.alpha != 1.f || p.residual || p.aux_out || p.act == Act::Gelu || p.epilogue == Epilogue::GeluBwdStore)
     return hipErrorInvalidValue;
   if (p.dtype == DType::F32) return launch_typed<float>(p, stream);
   return launch_typed<bf16_t>(p, stream);
+}
+
+bool gemm_pair_shares_launch(const GemmProblem& d, const GemmProblem& w) {
+  return d.dtype == DType::BF16 && w.dtype == DType::BF16 && operands_valid(d) && operands_valid(w) && gemm_dma_accepts(d) &&
+         gemm_dma_accepts(w) && gemm_dma_pair_accepts(d, w);
+}
+
+hipError_t launch_gemm_pair(const GemmProblem& d, const GemmProblem& w, hipStream_t stream) {
+  if (gemm_pair_shares_launch(d, w)) return launch_gemm_dma_pair(d, w, stream);
+  hipError_t e = launch_gemm(w, stream);
+  if (e != hipSuccess) return e;
+  return launch_gemm(d, stream);
 }
 
 }  // namespace spb

@@ -264,8 +264,43 @@ __device__ __forceinline__ void store_ragged(const GemmParams& p, const float* p
   }
 }
 
+// Per-column operands of the bfloat16 epilogue for the 8 columns a lane owns: loaded once per wave tile, and by
+// the small-product kernel before its tile loop so that their latency is not paid at the end.
+struct ColumnOperands {
+  u32x4 sc, bs;  // 8 bfloat16 each, unpacked where they are used so that requesting them early waits for nothing
+};
 template <int WN>
-__device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset, int rows = 32) {
+__device__ __forceinline__ void load_column_operands(const GemmParams& p, int col_base, int lane, ColumnOperands& o) {
+  const int n = col_base + (lane % (WN / 8)) * 8;
+  o.sc = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};  // ones
+  o.bs = u32x4{0u, 0u, 0u, 0u};
+  if (p.epilogue != (int)Epilogue::BiasAct || n + 8 > p.N) return;
+  if (p.col_scale) o.sc = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.col_scale) + n);
+  if (p.bias) o.bs = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.bias) + n);
+}
+
+// The per-element tensor of the bfloat16 epilogue (residual or mask) for the first two rows a lane owns: what the
+// small-product kernel, whose waves finish at most 16 rows each, requests before its tile loop.
+template <int WN>
+__device__ __forceinline__ void load_row_operands(const GemmParams& p, int piece_row, int col_base, int lane, u32x4 (&x)[2]) {
+  constexpr int kPerRow = WN / 8, kRowStep = 64 / kPerRow;
+  const int n = col_base + (lane % kPerRow) * 8;
+  const bool plain = p.epilogue == (int)Epilogue::BiasAct;
+  const bf16_t* xsrc = plain ? static_cast<const bf16_t*>(p.residual) : static_cast<const bf16_t*>(p.mask);
+  const int ldx = plain ? p.ldres : p.ldmask;
+  x[0] = u32x4{0u, 0u, 0u, 0u};
+  x[1] = x[0];
+  if (p.epilogue == (int)Epilogue::StoreF32 || xsrc == nullptr || n + 8 > p.N) return;
+#pragma unroll
+  for (int it = 0; it < 2; ++it)
+    x[it] = *reinterpret_cast<const u32x4*>(xsrc + (size_t)min(piece_row + lane / kPerRow + it * kRowStep, p.M - 1) * ldx + n);
+}
+
+// The row loops read PARTS partial tiles, part_stride floats apart, and add them up (one tile for the large
+// kernels, the four waves' partial sums for the small-product kernel).
+template <int WN, int PARTS = 1>
+__device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset,
+                                               int rows = 32, int part_stride = 0) {
   constexpr int kPitch = WN + 4;
   constexpr int kPerRow = WN / 4;             // 4-column units per row; 64 % kPerRow == 0, so a lane's column never changes
   const int c = (lane % kPerRow) * 4, n = col_base + c;
@@ -281,17 +316,22 @@ __device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float*
   for (int row = lane / kPerRow; row < rows; row += 64 / kPerRow) {
     const int m = piece_row + row;
     if (m >= p.M) break;
+    f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
+#pragma unroll
+    for (int w = 1; w < PARTS; ++w) v += *reinterpret_cast<const f32x4*>(stage + w * part_stride + row * kPitch + c);
     if (whole) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c) * p.alpha + b;
-      *reinterpret_cast<f32x4*>(static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n) = v;
+      *reinterpret_cast<f32x4*>(static_cast<float*>(p.C) + c_offset + (size_t)m * p.ldc + n) = v * p.alpha + b;
     } else {
-      store_ragged(p, stage + row * kPitch + c, 4, m, n, c_offset);
+      float t[4] = {v[0], v[1], v[2], v[3]};
+      store_ragged(p, t, 4, m, n, c_offset);
     }
   }
 }
 
-template <int WN>
-__device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset, int rows = 32) {
+template <int WN, int PARTS = 1>
+__device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset,
+                                                int rows = 32, int part_stride = 0, const ColumnOperands* preloaded = nullptr,
+                                                const u32x4* xpre = nullptr) {
   constexpr int kPitch = WN + 4;
   constexpr int kPerRow = WN / 8;             // 8-column units per row; a lane's column never changes
   constexpr int kRowStep = 64 / kPerRow;
@@ -305,20 +345,34 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
   const int ldx = plain ? p.ldres : p.ldmask;
   if (n + 8 > p.N) {
 #pragma unroll 1
-    for (int row = lane / kPerRow; row < rows && piece_row + row < p.M; row += kRowStep)
-      store_ragged(p, stage + row * kPitch + c, 8, piece_row + row, n, c_offset);
+    for (int row = lane / kPerRow; row < rows && piece_row + row < p.M; row += kRowStep) {
+      float t[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        t[e] = stage[row * kPitch + c + e];
+#pragma unroll
+        for (int w = 1; w < PARTS; ++w) t[e] += stage[w * part_stride + row * kPitch + c + e];
+      }
+      store_ragged(p, t, 8, piece_row + row, n, c_offset);
+    }
     return;
   }
+  ColumnOperands cols;
+  if (preloaded) cols = *preloaded;
+  else load_column_operands<WN>(p, col_base, lane, cols);
   float sc[8], bs[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) { sc[e] = 1.f; bs[e] = 0.f; }
-  if (plain && p.col_scale) unpack_bf16x8(*reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.col_scale) + n), sc);
-  if (plain && p.bias) unpack_bf16x8(*reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.bias) + n), bs);
+  unpack_bf16x8(cols.sc, sc);
+  unpack_bf16x8(cols.bs, bs);
   // One unit: 8 outputs of row `row` from the parked accumulators and the per-element tensor's chunk xcur.
   auto unit = [&](int row, int m, const u32x4& xcur) {
     float v[8], x[8], pre[8];
-    const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
-    const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+    f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
+    f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+#pragma unroll
+    for (int w = 1; w < PARTS; ++w) {
+      v0 += *reinterpret_cast<const f32x4*>(stage + w * part_stride + row * kPitch + c);
+      v1 += *reinterpret_cast<const f32x4*>(stage + w * part_stride + row * kPitch + c + 4);
+    }
     unpack_bf16x8(xcur, x);
 #pragma unroll
     for (int e = 0; e < 4; ++e) { v[e] = v0[e] * p.alpha; v[4 + e] = v1[e] * p.alpha; }
@@ -348,6 +402,14 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
     *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.C) + c_offset + (size_t)m * p.ldc + n) = pack_bf16x8(v);
   };
   const int row0 = lane / kPerRow;
+  if (xpre) {              // at most two rows per lane, their chunks already requested (see load_row_operands)
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int row = row0 + it * kRowStep;
+      if (row < rows && piece_row + row < p.M) unit(row, piece_row + row, xpre[it]);
+    }
+    return;
+  }
   if (xsrc == nullptr) {   // nothing to read per element: stores only, nothing to wait for
     const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll 1
@@ -520,27 +582,30 @@ __device__ __forceinline__ void wait_own_loads() {
   asm volatile("" ::: "memory");
 }
 
-template <int BM, int BN, Layout LA, Layout LB>
-__global__ __launch_bounds__(256) void gemm_bf16_small_kernel(GemmParams p) {
+// LDS of one small-product workgroup whose waves keep SW tiles each: the four rings, or the four parked
+// partial tiles where those need more.
+constexpr size_t small_product_lds(int bm, int bn, int sw) {
+  const size_t rings = (size_t)4 * sw * (bm + bn) * kRowBytes, parked = (size_t)4 * bm * (bn + 4) * 4;
+  return (rings > parked ? rings : parked + 1023) / 1024 * 1024;
+}
+
+template <int BM, int BN, int SW, Layout LA, Layout LB>
+__device__ __forceinline__ void small_product(const GemmParams& p, int block, int z, char* lds) {
   constexpr int NW = 4, TM = BM / 32, TN = BN / 32;
-  constexpr int kStageBytes = (BM + BN) * kRowBytes;
-  constexpr int SW = (BM + BN) <= 64 ? 4 : 2;   // ring depth per wave; four rings fill 128 KiB
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;  // SW of them per wave
   constexpr int kLoads = (BM + BN) / 8;        // direct-to-LDS instructions per tile (one wave loads a whole tile)
   constexpr int kPitch = BN + 4;               // floats per parked row; column BN carries the row sum of A
   constexpr int kRows = BM / NW;               // rows each wave finishes
   static_assert((BM == 32 || BM == 64) && (BN == 32 || BN == 64), "small tiles");
-  static_assert((size_t)NW * BM * kPitch * 4 <= (size_t)NW * SW * kStageBytes, "the four partial tiles fit in the rings");
-  static_assert(SW * kLoads < 64, "vmcnt range");
+  static_assert(SW >= 1 && SW * kLoads < 64, "vmcnt range");
 
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
+  const int tile = xcd_tile(block, p.tiles_m * p.tiles_n);
   const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   char* ring = lds + wave * (SW * kStageBytes);
 
-  const int z = blockIdx.y;  // batch entry, or slice of the k range
   int t_first = 0, t_end = (p.K + kTileK - 1) / kTileK;
   if (p.k_tiles_per_split > 0) {
     t_first = z * p.k_tiles_per_split;
@@ -562,6 +627,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(GemmParams p) {
 #pragma unroll
   for (int s = 0; s < SW; ++s)
     if (s < n) issue(s);
+
+  ColumnOperands cols;  // what the epilogue reads from global memory: requested now, used after the tile loop
+  u32x4 xpre[2];
+  static_assert(kRows <= 2 * (64 / (BN / 8)), "two epilogue rows per lane at most");
+  load_column_operands<BN>(p, n0, lane, cols);
+  load_row_operands<BN>(p, m0 + kRows * wave, n0, lane, xpre);
 
   f32x16 acc[TM][TN], acc_sum[TM];
 #pragma unroll
@@ -625,28 +696,53 @@ __global__ __launch_bounds__(256) void gemm_bf16_small_kernel(GemmParams p) {
     }
   }
   __syncthreads();
-  // wave w finishes rows kRows * w ..: sum of the four partials, in place in the first one
+  // wave w finishes rows kRows * w ..: the row loops add up the four partials
   const int row_base = kRows * wave;
-  constexpr int kUnits = kRows * (BN / 4) / 64;  // 16-byte units per lane
-  static_assert(kUnits >= 1, "a wave's rows fill its lanes");
-#pragma unroll
-  for (int q = 0; q < kUnits; ++q) {
-    const int idx = q * 64 + lane;
-    float* at = red + (row_base + idx / (BN / 4)) * kPitch + (idx % (BN / 4)) * 4;
-    f32x4 v = *reinterpret_cast<const f32x4*>(at);
-#pragma unroll
-    for (int w = 1; w < NW; ++w) v += *reinterpret_cast<const f32x4*>(at + w * (BM * kPitch));
-    *reinterpret_cast<f32x4*>(at) = v;
-  }
   if (want_row_sum && lane < kRows) {
     const float* at = red + (row_base + lane) * kPitch + BN;
     const float v = at[0] + at[BM * kPitch] + at[2 * BM * kPitch] + at[3 * BM * kPitch];
     if (m0 + row_base + lane < p.M) p.a_row_sum[m0 + row_base + lane] = v;
   }
   const float* stage = red + row_base * kPitch;
-  if (p.epilogue == (int)Epilogue::StoreF32) store_rows_f32<BN>(p, stage, m0 + row_base, n0, lane, batch_offset_z(p.c_batch, z), kRows);
-  else store_rows_bf16<BN>(p, stage, m0 + row_base, n0, lane, batch_offset_z(p.c_batch, z), kRows);
+  if (p.epilogue == (int)Epilogue::StoreF32) store_rows_f32<BN, NW>(p, stage, m0 + row_base, n0, lane, batch_offset_z(p.c_batch, z), kRows, BM * kPitch);
+  else store_rows_bf16<BN, NW>(p, stage, m0 + row_base, n0, lane, batch_offset_z(p.c_batch, z), kRows, BM * kPitch, &cols, xpre);
 }
+
+// Ring depth per wave: alone on its CU a workgroup's rings fill 128 KiB; the workgroups of a pair launch take
+// half, so that one of each product fits on a CU and their fixed latencies overlap.
+constexpr int small_ring_depth(int bm, int bn, bool paired) { return (int)((paired ? 64 : 128) * 1024 / (4 * (bm + bn) * kRowBytes)); }
+
+template <int BM, int BN, Layout LA, Layout LB>
+__global__ __launch_bounds__(256) void gemm_bf16_small_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  small_product<BM, BN, small_ring_depth(BM, BN, false), LA, LB>(p, blockIdx.x, blockIdx.y /* batch entry, or slice of the k range */, lds);
+}
+
+// Two independent small products in one launch (the input gradient and the weight gradient of a dense layer,
+// which both start from the same output gradient): the first product's tiles take the lower block indices.
+template <int BM1, int BN1, Layout LA1, Layout LB1, int BM2, int BN2, Layout LA2, Layout LB2>
+__global__ __launch_bounds__(256) void gemm_bf16_small_pair_kernel(GemmParams p1, GemmParams p2) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int n1 = p1.tiles_m * p1.tiles_n;
+  if ((int)blockIdx.x < n1) small_product<BM1, BN1, small_ring_depth(BM1, BN1, true), LA1, LB1>(p1, blockIdx.x, 0, lds);
+  else small_product<BM2, BN2, small_ring_depth(BM2, BN2, true), LA2, LB2>(p2, blockIdx.x - n1, 0, lds);
+}
+template <int BM1, int BN1, int BM2, int BN2>
+constexpr size_t small_pair_lds() {
+  const size_t a = small_product_lds(BM1, BN1, small_ring_depth(BM1, BN1, true)), b = small_product_lds(BM2, BN2, small_ring_depth(BM2, BN2, true));
+  return a > b ? a : b;
+}
+
+
+// Which products go to the small-product kernel, and with which tile.
+inline long tile_count(const GemmProblem& q, int tm, int tn) { return (long)((q.M + tm - 1) / tm) * ((q.N + tn - 1) / tn) * q.batch * q.k_splits; }
+inline bool small_product_fits(const GemmProblem& q) {
+  if (q.a_gather != Gather::None || q.b_gather != Gather::None) return false;
+  if (q.N <= 64 && q.M > 64) return tile_count(q, 256, 64) < 256;
+  if (q.M <= 64 && q.N > 64) return tile_count(q, 64, 256) < 256;
+  return tile_count(q, 256, 256) < 512 && tile_count(q, 128, 128) < 192;
+}
+inline bool small_product_tile64(const GemmProblem& q) { return tile_count(q, 64, 64) >= 192; }
 
 template <int BM, int BN, Layout LA, Layout LB>
 hipError_t launch_small(const GemmProblem& q, hipStream_t stream) {
@@ -658,7 +754,7 @@ hipError_t launch_small(const GemmProblem& q, hipStream_t stream) {
     p.c_batch.outer = (long long)q.M * q.ldc; p.c_batch.inner = 0; p.c_batch.inner_count = 1;
     grid_y = q.k_splits;
   }
-  constexpr size_t lds_bytes = 128 * 1024;
+  constexpr size_t lds_bytes = small_product_lds(BM, BN, small_ring_depth(BM, BN, false));
   auto kernel = gemm_bf16_small_kernel<BM, BN, LA, LB>;
   static bool raised = false;  // per instantiation
   if (!raised) {
@@ -698,10 +794,17 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
 // Tile choice.  A 256 x 256 tile reads half as many operand bytes per flop from L2 as a 128 x 128 one, which is
 // what large products need; it only pays once there are enough tiles for two rounds over the 256 CUs.  A
 // dimension of 64 or less (a 64-channel convolution) gets a 64-wide tile so that no matrix-core work is spent
-// on rows that do not exist.  Small products take 64 x 64 tiles and a deeper ring: they are bound by latency.
+// on rows that do not exist.  Products with too few tiles for that go to the small-product kernel (plain
+// operands) or to 64 x 64 tiles with a deeper ring (gathered operands): they are bound by latency.
 template <Layout LA, Layout LB, Gather GA = Gather::None, Gather GB = Gather::None>
 hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
-  auto tiles = [&](int tm, int tn) { return (long)((q.M + tm - 1) / tm) * ((q.N + tn - 1) / tn) * q.batch * q.k_splits; };
+  auto tiles = [&](int tm, int tn) { return tile_count(q, tm, tn); };
+  if constexpr (GA == Gather::None && GB == Gather::None) {
+    if (small_product_fits(q)) {
+      if (small_product_tile64(q)) return launch_small<64, 64, LA, LB>(q, stream);
+      return launch_small<32, 32, LA, LB>(q, stream);
+    }
+  }
   if (q.N <= 64 && q.M > 64) {
     if (tiles(256, 64) >= 256) return launch_tile<256, 64, 3, 4, 1, LA, LB, GA, GB>(q, stream);
     return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
@@ -712,10 +815,6 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   }
   if (tiles(256, 256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
   if (tiles(128, 128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
-  if constexpr (GA == Gather::None && GB == Gather::None) {
-    if (tiles(64, 64) >= 192) return launch_small<64, 64, LA, LB>(q, stream);
-    return launch_small<32, 32, LA, LB>(q, stream);
-  }
   return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
 }
 

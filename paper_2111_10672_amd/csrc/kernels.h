@@ -83,6 +83,13 @@ struct GemmProblem {
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
 bool gemm_dma_accepts(const GemmProblem& p);
 hipError_t launch_gemm_dma(const GemmProblem& p, hipStream_t stream);
+// The input-gradient product d (RowK x KRow) and the weight-gradient product w (KRow x KRow) of one dense layer,
+// which do not depend on each other: one launch when both are small enough for the small-product kernel
+// (gemm_pair_shares_launch says whether), otherwise w and then d, one launch each.
+bool gemm_pair_shares_launch(const GemmProblem& d, const GemmProblem& w);
+hipError_t launch_gemm_pair(const GemmProblem& d, const GemmProblem& w, hipStream_t stream);
+bool gemm_dma_pair_accepts(const GemmProblem& d, const GemmProblem& w);
+hipError_t launch_gemm_dma_pair(const GemmProblem& d, const GemmProblem& w, hipStream_t stream);
 double gemm_flops(const GemmProblem& p);
 double gemm_bytes(const GemmProblem& p);
 

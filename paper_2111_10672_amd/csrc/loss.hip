@@ -81,6 +81,46 @@ __global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ row
   if (threadIdx.x == 0) out[0] = ((red[0] + red[1]) + (red[2] + red[3])) / (float)rows;
 }
 
+// Few classes and few rows (a perceptron's 10-way head): everything in ONE workgroup and one launch.  A row takes
+// lpr lanes (the power of two that holds its classes), so a wave works on 64 / lpr rows at a time; the mean adds
+// each wave's rows in order and then the four waves in a fixed order.
+template <typename DZ>
+__global__ __launch_bounds__(256) void softmax_xent_one_block_kernel(const float* __restrict__ logits, int ldz,
+                                                                     const int32_t* __restrict__ labels, int rows, int classes, int lpr,
+                                                                     DZ* __restrict__ dz, int lddz, float* __restrict__ row_loss,
+                                                                     float* __restrict__ loss_out) {
+  __shared__ float red[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane % lpr, rows_per_wave = 64 / lpr;
+  const float inv_rows = 1.f / (float)rows;
+  float acc = 0.f;
+  for (int base = 0; base < rows; base += 4 * rows_per_wave) {
+    const int row = base + wave * rows_per_wave + lane / lpr;
+    const bool live = row < rows, mine = live && sub < classes;
+    const float z = mine ? logits[(size_t)row * ldz + sub] : -INFINITY;
+    float m = z;
+    for (int o = lpr >> 1; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    float s = mine ? expf(z - m) : 0.f;
+    for (int o = lpr >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (!live) continue;                       // no shuffles below
+    const float lse = m + logf(s);
+    const int y = labels[row];
+    DZ* out = dz + (size_t)row * lddz;
+    if (mine) store_dz(out + sub, (expf(z - lse) - (sub == y ? 1.f : 0.f)) * inv_rows);
+    for (int c = classes + sub; c < lddz; c += lpr) store_dz(out + c, 0.f);  // keep the pitch padding zero
+    if (sub == 0) {
+      // a label outside [0, classes) contributes no target term instead of reading out of bounds
+      const float l = lse - ((unsigned)y < (unsigned)classes ? logits[(size_t)row * ldz + y] : 0.f);
+      row_loss[row] = l;
+      acc += l;
+    }
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) loss_out[0] = ((red[0] + red[1]) + (red[2] + red[3])) * inv_rows;
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
 }
@@ -92,6 +132,15 @@ hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labe
                                hipStream_t stream) {
   if (!logits || !labels || !dz || !row_loss || !loss_out || rows <= 0 || classes <= 0 || ldz < classes || lddz < classes)
     return hipErrorInvalidValue;
+  if (classes <= 64 && rows <= 4096) {
+    int lpr = 1;
+    while (lpr < classes) lpr <<= 1;
+    if (dz_dtype == DType::F32)
+      hipLaunchKernelGGL((softmax_xent_one_block_kernel<float>), dim3(1), dim3(256), 0, stream, logits, ldz, labels, rows, classes, lpr, (float*)dz, lddz, row_loss, loss_out);
+    else
+      hipLaunchKernelGGL((softmax_xent_one_block_kernel<uint16_t>), dim3(1), dim3(256), 0, stream, logits, ldz, labels, rows, classes, lpr, (uint16_t*)dz, lddz, row_loss, loss_out);
+    return hipGetLastError();
+  }
   const bool wide = classes > 2048;
   const int grid = wide ? rows : (rows + 3) / 4;
   if (dz_dtype == DType::F32) {

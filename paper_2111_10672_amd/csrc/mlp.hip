@@ -120,8 +120,10 @@ class MlpModel : public Model {
       w.a_row_sum = static_cast<float*>(grad_ptrs[2 * u + 1]);
       w.a_pad_zero = w.b_pad_zero = true;  // dz: padding zeroed by its producer; activations have none
       w.name = dtype == DType::F32 ? "gemm_f32_wgrad" : "gemm_bf16_wgrad";
-      if (int rc = gemm(w, s)) return rc;
-      if (u == L - k) break;  // lowest visited unit: no input gradient (nothing below consumes it)
+      if (u == L - k) {  // lowest visited unit: no input gradient (nothing below consumes it)
+        if (int rc = gemm(w, s)) return rc;
+        break;
+      }
       GemmProblem d;  // dz_{u-1}[b, i] = (sum_n dz[b, n] * W_u[n, i]) * [a_u[b, i] > 0]
       d.dtype = dtype; d.a_layout = Layout::RowK; d.b_layout = Layout::KRow;
       d.M = batch_; d.N = n_in; d.K = n_out;
@@ -130,7 +132,7 @@ class MlpModel : public Model {
       d.epilogue = Epilogue::MaskStore; d.mask = a_u; d.ldmask = ld_a;
       d.a_pad_zero = d.b_pad_zero = true;
       d.name = dtype == DType::F32 ? "gemm_f32_dgrad" : "gemm_bf16_dgrad";
-      if (int rc = gemm(d, s)) return rc;
+      if (int rc = gemm_pair(d, w, s)) return rc;  // independent of each other: one launch where both are small
       dz = d.C; ld_dz = d.ldc;
     }
     return SPB_OK;

@@ -62,11 +62,13 @@ class Model {
   int stashed_k = -1;  // depth the last forward pass stashed for; -1 = no forward yet
   void* ws = nullptr;
   KernelTimer timer;
-  std::map<std::string, GemmProblem> last_product;  // per kernel class, the most recent product (kept while timing is on)
+  struct Product { GemmProblem first, second; bool pair = false; };
+  std::map<std::string, Product> last_product;  // per kernel class, the most recent product or pair (kept while timing is on)
   int replay(const char* name, int count, hipStream_t s);
 
  protected:
   int gemm(const GemmProblem& p, hipStream_t s);
+  int gemm_pair(const GemmProblem& d, const GemmProblem& w, hipStream_t s);  // see launch_gemm_pair
   int run(const char* name, double bytes, hipStream_t s, const std::function<hipError_t()>& launch);
   int check(hipError_t e, const char* what);
 };
