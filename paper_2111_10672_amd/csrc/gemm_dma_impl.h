@@ -73,11 +73,21 @@ struct TileSource {
   int tap[kInstr], chan[kInstr];           // ConvRows, ConvWeightT: where this lane's k of the next tile falls; ConvPatchT: fixed (tap, ci) of its rows
   int g0[kInstr], g1[kInstr], g2[kInstr];  // ConvRows: pixel base, row term, column term.  ConvPatchT: image, pixel in image of the next tile's k-row.
   int step_q, step_r;                      // one tile further: quotient and remainder of 64 by the modulus being stepped
+  // ConvRows whose channel count is a multiple of the tile's k (and, transposed, stride 1): a whole tile lies on
+  // ONE tap, so the tap and its offset are wave-uniform scalars and a lane only adds them to the address of its
+  // pixel (ptr[] then holds that address, at tap (0, 0)) and checks its two coordinates.
+  bool one_tap;
+  int u_tap, u_chan;
 
   __device__ __forceinline__ void init(const bf16_t* base, int ld, int row0, int nrows, int wave, int lane, int t0, const ConvGeom& cg) {
     tile_step = L == Layout::RowK ? (size_t)kTileK * 2 : (size_t)kTileK * ld * 2;
     const int modulus = G == Gather::ConvRows ? cg.sc : G == Gather::ConvWeightT ? cg.w_cout : cg.rh * cg.rw;
     if constexpr (G != Gather::None) { step_q = kTileK / modulus; step_r = kTileK % modulus; }
+    one_tap = false;
+    if constexpr (G == Gather::ConvRows) {
+      one_tap = cg.sc % kTileK == 0 && (!cg.transposed || cg.stride == 1);
+      u_tap = (t0 * kTileK) / cg.sc; u_chan = (t0 * kTileK) % cg.sc;
+    }
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) {
       const int slot = (i * NW + wave) * 64 + lane;
@@ -108,6 +118,7 @@ struct TileSource {
           g1[i] = cg.transposed ? a + cg.pad : a * cg.stride - cg.pad;
           g2[i] = cg.transposed ? b + cg.pad : b * cg.stride - cg.pad;
           tap[i] = k_abs / cg.sc; chan[i] = k_abs - tap[i] * cg.sc;
+          if (one_tap) ptr[i] += ((long long)(g0[i] + g1[i] * cg.sw + g2[i]) * cg.sc + k) * 2;
         } else if constexpr (G == Gather::ConvWeightT) {  // row gr = ci; k = (tap, co)
           tap[i] = k_abs / cg.w_cout; chan[i] = k_abs - tap[i] * cg.w_cout;
         } else {                                          // row gr = (tap, ci); k = output pixel m
@@ -121,6 +132,23 @@ struct TileSource {
 
   // Issue tile t (tiles must be issued in increasing order, one after the other).
   __device__ __forceinline__ void issue(int t, int K, char* tile, int wave, int ld, const ConvGeom& cg) {
+    if constexpr (G == Gather::ConvRows) {
+      if (one_tap) {
+        const int r = (u_tap * (65536 / cg.s + 1)) >> 16, c = u_tap - r * cg.s;   // tap = r * S + c, exact for tap < 256
+        const int dr = cg.transposed ? -r : r, dc = cg.transposed ? -c : c;
+        const long long tap_bytes = ((long long)(dr * cg.sw + dc) * cg.sc + u_chan) * 2;
+        const bool tap_ok = u_tap < cg.r * cg.s;
+#pragma unroll
+        for (int i = 0; i < kInstr; ++i) {
+          const bool ok = tap_ok && in_rows[i] && (unsigned)(g1[i] + dr) < (unsigned)cg.sh && (unsigned)(g2[i] + dc) < (unsigned)cg.sw;
+          const char* src = ok ? ptr[i] + tap_bytes : reinterpret_cast<const char*>(kZeroChunk);
+          __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, 0, 0);
+        }
+        u_chan += kTileK;
+        if (u_chan >= cg.sc) { u_chan = 0; ++u_tap; }
+        return;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) {
       const char* src = reinterpret_cast<const char*>(kZeroChunk);

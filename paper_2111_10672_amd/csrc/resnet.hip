@@ -222,11 +222,14 @@ class ResnetModel : public Model {
     return g;
   }
 
+  // A 1x1 convolution with stride 1 is a plain matrix product over the pixel rows: no gather at all.
+  static bool pointwise(const Conv& c) { return c.k == 1 && c.stride == 1 && c.pad == 0 && c.cin_eff == c.cin; }
+
   // out = act(scale * conv(x, w) + shift + residual); y_keep (optional) receives the pre-affine output
   int conv_forward(const Conv& c, const void* x, const void* w, void* y_keep, const void* residual, bool relu, void* out, hipStream_t s) {
     GemmProblem g;
     g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::RowK; g.epilogue = Epilogue::BiasAct;
-    g.a_gather = Gather::ConvRows; g.conv = geom(c);
+    if (!pointwise(c)) { g.a_gather = Gather::ConvRows; g.conv = geom(c); }
     g.M = (int)c.out_rows(batch_); g.N = c.cout; g.K = c.k_total();
     g.A = x; g.lda = g.K; g.B = w; g.ldb = g.K; g.C = out; g.ldc = c.cout;
     g.col_scale = param_ptrs[c.scale]; g.bias = param_ptrs[c.shift];
@@ -240,10 +243,12 @@ class ResnetModel : public Model {
   int conv_dgrad(const Conv& c, const void* dy, const void* w, const void* residual, void* dx, hipStream_t s) {
     GemmProblem g;
     g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::KRow; g.epilogue = Epilogue::BiasAct;
-    g.a_gather = Gather::ConvRows; g.b_gather = Gather::ConvWeightT;
-    g.conv.n = batch_; g.conv.sh = c.out_h; g.conv.sw = c.out_w; g.conv.sc = c.cout; g.conv.rh = c.in_h; g.conv.rw = c.in_w;
-    g.conv.r = c.k; g.conv.s = c.k; g.conv.stride = c.stride; g.conv.pad = c.pad; g.conv.transposed = 1;
-    g.conv.w_cin = c.cin_eff; g.conv.w_cout = c.cout;
+    if (!pointwise(c)) {
+      g.a_gather = Gather::ConvRows; g.b_gather = Gather::ConvWeightT;
+      g.conv.n = batch_; g.conv.sh = c.out_h; g.conv.sw = c.out_w; g.conv.sc = c.cout; g.conv.rh = c.in_h; g.conv.rw = c.in_w;
+      g.conv.r = c.k; g.conv.s = c.k; g.conv.stride = c.stride; g.conv.pad = c.pad; g.conv.transposed = 1;
+      g.conv.w_cin = c.cin_eff; g.conv.w_cout = c.cout;
+    }
     g.M = (int)c.in_rows(batch_); g.N = c.cin_eff; g.K = c.k * c.k * c.cout;
     g.A = dy; g.lda = g.K; g.B = w; g.ldb = c.cin_eff; g.C = dx; g.ldc = c.cin_eff;
     g.residual = residual; g.ldres = c.cin_eff;
@@ -254,7 +259,7 @@ class ResnetModel : public Model {
   int conv_wgrad(const Conv& c, const void* x, const void* dy, float* partial, float* dw, hipStream_t s) {
     GemmProblem g;
     g.dtype = dtype; g.a_layout = Layout::KRow; g.b_layout = Layout::KRow; g.epilogue = Epilogue::StoreF32;
-    g.b_gather = Gather::ConvPatchT; g.conv = geom(c);
+    if (!pointwise(c)) { g.b_gather = Gather::ConvPatchT; g.conv = geom(c); }
     g.M = c.cout; g.N = c.k_total(); g.K = (int)c.out_rows(batch_);
     g.A = dy; g.lda = c.cout; g.B = x; g.ldb = g.N; g.C = partial; g.ldc = g.N;
     g.k_splits = wgrad_splits(c);
