@@ -52,14 +52,14 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
   const long long first = (long long)blockIdx.x * rows_per_block;
   const long long last = min(rows, first + rows_per_block);
   if (active) {
-    for (long long r = first + lane_row; r < last; r += rows_per_pass) {
-      const size_t off = (size_t)r * channels + chunk * 8;
+    // two rows per trip, all their loads requested before the first is used
+    auto finish = [&](size_t off, const u32x4& dw, const u32x4& yw, const u32x4& aw) {
       float d[8], yv[8], o[8];
-      unpack8(*reinterpret_cast<const u32x4*>(dout + off), d);
-      unpack8(*reinterpret_cast<const u32x4*>(y + off), yv);
+      unpack8(dw, d);
+      unpack8(yw, yv);
       if (act) {
         float a[8];
-        unpack8(*reinterpret_cast<const u32x4*>(act + off), a);
+        unpack8(aw, a);
 #pragma unroll
         for (int e = 0; e < 8; ++e) if (!(a[e] > 0.f)) d[e] = 0.f;
       }
@@ -67,6 +67,21 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
       for (int e = 0; e < 8; ++e) { s1[e] += d[e] * yv[e]; s0[e] += d[e]; o[e] = sc[e] * d[e]; }
       *reinterpret_cast<u32x4*>(dy + off) = pack8(o);
       if (dsum) *reinterpret_cast<u32x4*>(dsum + off) = pack8(d);
+    };
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    long long r = first + lane_row;
+    for (; r + rows_per_pass < last; r += 2 * rows_per_pass) {
+      const size_t off0 = (size_t)r * channels + chunk * 8, off1 = off0 + (size_t)rows_per_pass * channels;
+      const u32x4 d0 = *reinterpret_cast<const u32x4*>(dout + off0), d1 = *reinterpret_cast<const u32x4*>(dout + off1);
+      const u32x4 y0 = *reinterpret_cast<const u32x4*>(y + off0), y1 = *reinterpret_cast<const u32x4*>(y + off1);
+      const u32x4 a0 = act ? *reinterpret_cast<const u32x4*>(act + off0) : zero, a1 = act ? *reinterpret_cast<const u32x4*>(act + off1) : zero;
+      finish(off0, d0, y0, a0);
+      finish(off1, d1, y1, a1);
+    }
+    if (r < last) {
+      const size_t off = (size_t)r * channels + chunk * 8;
+      finish(off, *reinterpret_cast<const u32x4*>(dout + off), *reinterpret_cast<const u32x4*>(y + off),
+             act ? *reinterpret_cast<const u32x4*>(act + off) : zero);
     }
     float* mine = sh + ((size_t)lane_row * chunks + chunk) * 16;
 #pragma unroll
@@ -106,6 +121,24 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   const long long src = cin == cin_padded ? j : (j / cin) * cin_padded + (j % cin);
   float s = 0.f;
   for (int z = 0; z < slices; ++z) s += partial[(size_t)z * slice_stride + src];
+  out[j] = s;
+}
+
+// The same for tensors without channel padding, four neighbouring elements per thread and four slices requested
+// at a time (the additions still run in slice order).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const f32x4* __restrict__ partial, int slices, long long slice_stride4,
+                                                             f32x4* __restrict__ out, long long numel4) {
+  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (j >= numel4) return;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  int z = 0;
+  for (; z + 4 <= slices; z += 4) {
+    const f32x4 a = partial[(size_t)z * slice_stride4 + j], b = partial[(size_t)(z + 1) * slice_stride4 + j];
+    const f32x4 c = partial[(size_t)(z + 2) * slice_stride4 + j], d = partial[(size_t)(z + 3) * slice_stride4 + j];
+    s += a; s += b; s += c; s += d;
+  }
+  for (; z < slices; ++z) s += partial[(size_t)z * slice_stride4 + j];
   out[j] = s;
 }
 
@@ -220,6 +253,12 @@ hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void*
 hipError_t launch_splitk_reduce(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,
                                 hipStream_t s) {
   if (!partial || !out || slices < 1 || numel <= 0 || cin <= 0 || cin_padded < cin) return hipErrorInvalidValue;
+  if (cin == cin_padded && numel % 4 == 0 && slice_stride % 4 == 0 && (reinterpret_cast<uintptr_t>(partial) & 15) == 0 &&
+      (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+    hipLaunchKernelGGL(splitk_reduce4_kernel, dim3(blocks_for(numel / 4)), dim3(256), 0, s, reinterpret_cast<const f32x4*>(partial), slices,
+                       slice_stride / 4, reinterpret_cast<f32x4*>(out), numel / 4);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(numel)), dim3(256), 0, s, partial, slices, slice_stride, out, numel, cin, cin_padded);
   return hipGetLastError();
 }

@@ -89,15 +89,16 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const uint16_t* __re
   if (lane == 0) { stats[2 * r] = mean; stats[2 * r + 1] = rstd; }
 }
 
-// LayerNorm backward for rows r0 .. r0+31 of this workgroup (8 per wavefront):
+// LayerNorm backward for rows r0 .. r0+7 of this workgroup (2 per wavefront, so that the row loop is short and
+// a matrix of a few thousand rows still fills the chip):
 //   g = dy * gamma;  dx = (g - mean(g) - xhat * mean(g * xhat)) * rstd (+ res);  partial sums of dy * xhat and dy per column.
-constexpr int kLnRowsPerBlock = 32;
+constexpr int kLnRowsPerBlock = 8;
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const uint16_t* __restrict__ dy, int lddy, const uint16_t* __restrict__ x,
                                                             int ldx, const int32_t* __restrict__ rows, const float* __restrict__ stats,
                                                             const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ res, int ldres,
                                                             uint16_t* __restrict__ dx, int lddx, float* __restrict__ partial,
                                                             int n_rows, int width) {
-  extern __shared__ float sh[];  // [2][width]
+  extern __shared__ float sh[];  // [4 wavefronts][2][width]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int chunks = width >> 3;
   float dgam[kMaxChunks][8], dbet[kMaxChunks][8], gam[kMaxChunks][8];
@@ -150,47 +151,69 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const uint16_t* __re
     }
   }
   // add the four wavefronts' column sums in wavefront order
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
+  float* mine = sh + (size_t)wave * 2 * width;
 #pragma unroll
-      for (int i = 0; i < kMaxChunks; ++i) {
-        const int c = lane + 64 * i;
-        if (c < chunks) {
+  for (int i = 0; i < kMaxChunks; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int col = c * 8 + e;
-            sh[col] = (w == 0 ? 0.f : sh[col]) + dgam[i][e];
-            sh[width + col] = (w == 0 ? 0.f : sh[width + col]) + dbet[i][e];
-          }
-        }
-      }
+      for (int e = 0; e < 8; ++e) { mine[c * 8 + e] = dgam[i][e]; mine[width + c * 8 + e] = dbet[i][e]; }
     }
-    __syncthreads();
   }
-  for (int col = threadIdx.x; col < 2 * width; col += 256) partial[(size_t)blockIdx.x * 2 * width + col] = sh[col];
+  __syncthreads();
+  for (int col = threadIdx.x; col < 2 * width; col += 256)
+    partial[(size_t)blockIdx.x * 2 * width + col] = ((sh[col] + sh[2 * width + col]) + sh[4 * width + col]) + sh[6 * width + col];
 }
 
-// out_a[c] = sum_b partial[b][0][c];  out_b[c] = sum_b partial[b][1][c].  One wavefront per column: lane l adds blocks
-// l, l + 64, ... in order, then the lane sums are combined by a fixed shuffle tree (same bits on every run).
+// out_a[c] = sum_b partial[b][0][c];  out_b[c] = sum_b partial[b][1][c].  A workgroup takes 16 columns: thread
+// (g, c) adds blocks g, g + 16, ... of column c in order (16 neighbouring threads read 64 contiguous bytes), then
+// the 16 group sums of a column are added in group order: the same bits on every run.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int n_blocks, int width,
                                                               float* __restrict__ out_a, float* __restrict__ out_b) {
-  const int lane = threadIdx.x & 63, col = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (col >= 2 * width) return;
+  __shared__ float sh[16][17];
+  const int c = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int col = blockIdx.x * 16 + c;
   float s = 0.f;
-  for (int b = lane; b < n_blocks; b += 64) s += partial[(size_t)b * 2 * width + col];
-  s = wave_sum(s);
-  if (lane == 0) {
-    if (col < width) out_a[col] = s;
-    else out_b[col - width] = s;
+  if (col < 2 * width)
+    for (int b = g; b < n_blocks; b += 16) s += partial[(size_t)b * 2 * width + col];
+  sh[g][c] = s;
+  __syncthreads();
+  if (threadIdx.x < 16 && col < 2 * width) {
+    float t = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) t += sh[q][c];
+    if (col < width) out_a[col] = t;
+    else out_b[col - width] = t;
   }
 }
 
-// p[r, :] = softmax(s[r, :]) in bfloat16; one wavefront per row.
+// p[r, :] = softmax(s[r, :]) in bfloat16; one wavefront per row.  A row of up to 64 * kSoftmaxRegs scores is read
+// once and kept in registers (attention rows are a few hundred long); longer rows are re-read from cache.
+constexpr int kSoftmaxRegs = 8;
 __global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restrict__ s, uint16_t* __restrict__ p, long long n_rows, int len) {
   const int lane = threadIdx.x & 63;
   const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= n_rows) return;
   const float* in = s + r * len;
+  if (len <= 64 * kSoftmaxRegs) {
+    float v[kSoftmaxRegs];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < kSoftmaxRegs; ++i) {
+      const int c = lane + 64 * i;
+      v[i] = c < len ? in[c] : -INFINITY;
+      m = fmaxf(m, v[i]);
+    }
+    m = wave_max(m);
+    float z = 0.f;
+#pragma unroll
+    for (int i = 0; i < kSoftmaxRegs; ++i) { v[i] = lane + 64 * i < len ? expf(v[i] - m) : 0.f; z += v[i]; }
+    const float inv = 1.f / wave_sum(z);
+#pragma unroll
+    for (int i = 0; i < kSoftmaxRegs; ++i)
+      if (lane + 64 * i < len) p[r * len + lane + 64 * i] = to_bf16(v[i] * inv);
+    return;
+  }
   float m = -INFINITY;
   for (int c = lane; c < len; c += 64) m = fmaxf(m, in[c]);
   m = wave_max(m);
@@ -200,12 +223,28 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restric
   for (int c = lane; c < len; c += 64) p[r * len + c] = to_bf16(expf(in[c] - m) * inv);
 }
 
-// ds[r, :] = p * (dp - sum(dp * p)) * scale in bfloat16; one wavefront per row.
+// ds[r, :] = p * (dp - sum(dp * p)) * scale in bfloat16; one wavefront per row, same register scheme.
 __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* __restrict__ dp, const uint16_t* __restrict__ p,
                                                           uint16_t* __restrict__ ds, long long n_rows, int len, float scale) {
   const int lane = threadIdx.x & 63;
   const long long r = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= n_rows) return;
+  if (len <= 64 * kSoftmaxRegs) {
+    float d[kSoftmaxRegs], pv[kSoftmaxRegs];
+    float dot = 0.f;
+#pragma unroll
+    for (int i = 0; i < kSoftmaxRegs; ++i) {
+      const int c = lane + 64 * i;
+      d[i] = c < len ? dp[r * len + c] : 0.f;
+      pv[i] = c < len ? __uint_as_float(((uint32_t)p[r * len + c]) << 16) : 0.f;
+      dot += d[i] * pv[i];
+    }
+    dot = wave_sum(dot);
+#pragma unroll
+    for (int i = 0; i < kSoftmaxRegs; ++i)
+      if (lane + 64 * i < len) ds[r * len + lane + 64 * i] = to_bf16(pv[i] * (d[i] - dot) * scale);
+    return;
+  }
   float dot = 0.f;
   for (int c = lane; c < len; c += 64) dot += dp[r * len + c] * __uint_as_float(((uint32_t)p[r * len + c]) << 16);
   dot = wave_sum(dot);
@@ -214,7 +253,6 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* __restric
     ds[r * len + c] = to_bf16(pv * (dp[r * len + c] - dot) * scale);
   }
 }
-
 // x0[m, :] = tok[ids[m], :] + pos[m % seq, :].  An id outside [0, vocab) is clamped into range.
 __global__ __launch_bounds__(256) void embedding_fwd_kernel(const int32_t* __restrict__ ids, const uint16_t* __restrict__ tok,
                                                             const uint16_t* __restrict__ pos, uint16_t* __restrict__ out, int ldo,
@@ -310,12 +348,12 @@ hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx
   if (!row_ok(width, lddy) || !row_ok(width, ldx) || (dx && !row_ok(width, lddx)) || (res && !row_ok(width, ldres))) return hipErrorInvalidValue;
   if (!a16(dy) || !a16(x) || !a16(gamma) || !a16(dx) || !a16(res)) return hipErrorInvalidValue;
   const int blocks = (n_rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
-  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(blocks), dim3(256), (size_t)2 * width * sizeof(float), s, (const uint16_t*)dy, lddy,
+  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(blocks), dim3(256), (size_t)8 * width * sizeof(float), s, (const uint16_t*)dy, lddy,
                      (const uint16_t*)x, ldx, rows, stats, (const uint16_t*)gamma, (const uint16_t*)res, ldres, (uint16_t*)dx, lddx,
                      partial, n_rows, width);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 3) / 4), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 15) / 16), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
   return hipGetLastError();
 }
 
