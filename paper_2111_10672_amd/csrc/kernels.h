@@ -83,6 +83,9 @@ struct GemmProblem {
 hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream);
 bool gemm_dma_accepts(const GemmProblem& p);
 hipError_t launch_gemm_dma(const GemmProblem& p, hipStream_t stream);
+// float32 products of small dense layers (latency-bound): see gemm_f32_small.hip
+bool gemm_f32_small_accepts(const GemmProblem& p);
+hipError_t launch_gemm_f32_small(const GemmProblem& p, hipStream_t stream);
 // The input-gradient product d (RowK x KRow) and the weight-gradient product w (KRow x KRow) of one dense layer,
 // which do not depend on each other: one launch when both are small enough for the small-product kernel
 // (gemm_pair_shares_launch says whether), otherwise w and then d, one launch each.
