@@ -121,54 +121,6 @@ __global__ __launch_bounds__(256) void softmax_xent_one_block_kernel(const float
   if (threadIdx.x == 0) loss_out[0] = ((red[0] + red[1]) + (red[2] + red[3])) * inv_rows;
 }
 
-// The same single launch for wider heads whose logits fit in LDS (rows * classes floats): one workgroup of 16
-// wavefronts copies the logits in with all its loads in flight at once (a single workgroup that walked the rows
-// through global memory would pay one memory latency per row and pass), then takes a wavefront per row (rows w,
-// w + 16, ...), the lanes striding over the classes.
-__global__ __launch_bounds__(1024) void softmax_xent_one_block_wide_kernel(const float* __restrict__ logits, int ldz,
-                                                                           const int32_t* __restrict__ labels, int rows, int classes,
-                                                                           uint16_t* __restrict__ dz16, float* __restrict__ dz32, int lddz,
-                                                                           float* __restrict__ row_loss, float* __restrict__ loss_out) {
-  extern __shared__ float zs[];  // [rows][classes]
-  __shared__ float red[16];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int total = rows * classes;
-  for (int i = threadIdx.x; i < total; i += 1024) zs[i] = logits[(size_t)(i / classes) * ldz + i % classes];
-  __syncthreads();
-  const float inv_rows = 1.f / (float)rows;
-  float acc = 0.f;
-  for (int row = wave; row < rows; row += 16) {
-    const float* z = zs + row * classes;
-    float m = -INFINITY;
-    for (int c = lane; c < classes; c += 64) m = fmaxf(m, z[c]);
-    m = wave_max(m);
-    float s = 0.f;
-    for (int c = lane; c < classes; c += 64) s += expf(z[c] - m);
-    s = wave_sum(s);
-    const float lse = m + logf(s);
-    const int y = labels[row];
-    for (int c = lane; c < lddz; c += 64) {
-      const float g = c < classes ? (expf(z[c] - lse) - (c == y ? 1.f : 0.f)) * inv_rows : 0.f;  // pitch padding stays zero
-      if (dz16) store_dz(dz16 + (size_t)row * lddz + c, g);
-      else store_dz(dz32 + (size_t)row * lddz + c, g);
-    }
-    if (lane == 0) {
-      // a label outside [0, classes) contributes no target term instead of reading out of bounds
-      const float l = lse - ((unsigned)y < (unsigned)classes ? z[y] : 0.f);
-      row_loss[row] = l;
-      acc += l;
-    }
-  }
-  if (lane == 0) red[wave] = acc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    float t = 0.f;
-#pragma unroll
-    for (int w = 0; w < 16; ++w) t += red[w];
-    loss_out[0] = t * inv_rows;
-  }
-}
-
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* __restrict__ p, size_t words) {
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
 }
@@ -187,19 +139,6 @@ hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labe
       hipLaunchKernelGGL((softmax_xent_one_block_kernel<float>), dim3(1), dim3(256), 0, stream, logits, ldz, labels, rows, classes, lpr, (float*)dz, lddz, row_loss, loss_out);
     else
       hipLaunchKernelGGL((softmax_xent_one_block_kernel<uint16_t>), dim3(1), dim3(256), 0, stream, logits, ldz, labels, rows, classes, lpr, (uint16_t*)dz, lddz, row_loss, loss_out);
-    return hipGetLastError();
-  }
-  if ((long long)rows * classes * 4 <= 96 * 1024) {
-    static bool raised = false;
-    if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(softmax_xent_one_block_wide_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-      if (e != hipSuccess) return e;
-      raised = true;
-    }
-    hipLaunchKernelGGL(softmax_xent_one_block_wide_kernel, dim3(1), dim3(1024), (size_t)rows * classes * 4, stream, logits, ldz, labels, rows,
-                       classes, dz_dtype == DType::F32 ? nullptr : (uint16_t*)dz, dz_dtype == DType::F32 ? (float*)dz : nullptr, lddz, row_loss,
-                       loss_out);
     return hipGetLastError();
   }
   const bool wide = classes > 2048;
