@@ -2,6 +2,8 @@
 // the backward of "per-channel affine -> ReLU" with its per-channel reductions, the pools, channel padding of
 // the 3-channel input, and the fixed-order sum of split-k partial products.  Each moves every tensor through
 // HBM once, in 16-byte pieces along the channel index.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace spb {
@@ -35,16 +37,21 @@ __device__ __forceinline__ uint16_t to_bf16(float v) {
 // Backward of z = scale * y + shift followed by an optional ReLU whose output is `act`:
 //   dz = dout * [act > 0]   (dz = dout without act);   dy = scale * dz;   dsum = dz (optional)
 //   partial[block][0][c] = sum over the block's rows of dz * y;   partial[block][1][c] = sum of dz
-// Thread t owns chunk t % chunks of rows (t / chunks), (t / chunks) + rows_per_pass, ...
+// A workgroup takes a range of rows (blockIdx.x) of a slab of at most 256 channels (blockIdx.y), so that wide
+// tensors still give many workgroups while the partial sums stay small next to the tensor.  Thread t owns chunk
+// t % slab_chunks of the slab, rows (t / slab_chunks), (t / slab_chunks) + rows_per_pass, ...
+constexpr int kAffineSlabChunks = 32;
 __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __restrict__ dout, const uint16_t* __restrict__ act,
                                                               const uint16_t* __restrict__ y, const uint16_t* __restrict__ scale,
                                                               uint16_t* __restrict__ dy, uint16_t* __restrict__ dsum,
                                                               float* __restrict__ partial, long long rows, int channels, int rows_per_block) {
-  extern __shared__ float sh[];  // [rows_per_pass][chunks][16]
+  extern __shared__ float sh[];  // [rows_per_pass][slab_chunks][16]
   const int chunks = channels >> 3;
-  const int rows_per_pass = 256 / chunks;
-  const int chunk = threadIdx.x % chunks, lane_row = threadIdx.x / chunks;
-  const bool active = lane_row < rows_per_pass;
+  const int slab_chunks = min(chunks, kAffineSlabChunks);
+  const int rows_per_pass = 256 / slab_chunks;
+  const int local_chunk = threadIdx.x % slab_chunks, lane_row = threadIdx.x / slab_chunks;
+  const int chunk = blockIdx.y * slab_chunks + local_chunk;
+  const bool active = lane_row < rows_per_pass && chunk < chunks;
   float s1[8], s0[8], sc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { s1[e] = 0.f; s0[e] = 0.f; sc[e] = 0.f; }
@@ -83,17 +90,22 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
       finish(off, *reinterpret_cast<const u32x4*>(dout + off), *reinterpret_cast<const u32x4*>(y + off),
              act ? *reinterpret_cast<const u32x4*>(act + off) : zero);
     }
-    float* mine = sh + ((size_t)lane_row * chunks + chunk) * 16;
+  }
+  if (lane_row < rows_per_pass) {  // lanes past the tensor's last chunk park zeros
+    float* mine = sh + ((size_t)lane_row * slab_chunks + local_chunk) * 16;
 #pragma unroll
     for (int e = 0; e < 8; ++e) { mine[e] = s1[e]; mine[8 + e] = s0[e]; }
   }
   __syncthreads();
   // column sums over the block's row lanes, in lane order
-  for (int col = threadIdx.x; col < 2 * channels; col += 256) {
-    const int which = col / channels, c = col % channels;
+  const int slab_cols = slab_chunks * 8;
+  for (int col = threadIdx.x; col < 2 * slab_cols; col += 256) {
+    const int which = col / slab_cols, c = col % slab_cols;
+    const int channel = blockIdx.y * slab_cols + c;
+    if (channel >= channels) continue;
     float acc = 0.f;
-    for (int l = 0; l < rows_per_pass; ++l) acc += sh[((size_t)l * chunks + (c >> 3)) * 16 + which * 8 + (c & 7)];
-    partial[(size_t)blockIdx.x * 2 * channels + col] = acc;
+    for (int l = 0; l < rows_per_pass; ++l) acc += sh[((size_t)l * slab_chunks + (c >> 3)) * 16 + which * 8 + (c & 7)];
+    partial[((size_t)blockIdx.x * 2 + which) * channels + channel] = acc;
   }
 }
 
@@ -223,11 +235,14 @@ unsigned blocks_for(long long n) { return (unsigned)((n + 255) / 256); }
 }  // namespace
 
 // rows handled by one workgroup of the affine backward kernel, and the size of its partial buffer
+static int affine_slab_chunks(int channels) { return std::min(channels >> 3, kAffineSlabChunks); }
+static int affine_slabs(int channels) { return ((channels >> 3) + affine_slab_chunks(channels) - 1) / affine_slab_chunks(channels); }
 static int affine_rows_per_block(long long rows, int channels) {
-  const int per_pass = 256 / (channels >> 3);
-  long long want = (rows + 1023) / 1024;                      // about a thousand workgroups
+  const int per_pass = 256 / affine_slab_chunks(channels);
+  const long long row_blocks = std::max(1, 1024 / affine_slabs(channels));  // about a thousand workgroups in all
+  long long want = (rows + row_blocks - 1) / row_blocks;
   want = (want + per_pass - 1) / per_pass * per_pass;
-  return (int)(want < per_pass ? per_pass : want);
+  return (int)std::max<long long>(want, 4LL * per_pass);
 }
 size_t affine_partial_floats(long long rows, int channels) {
   const int rpb = affine_rows_per_block(rows, channels);
@@ -240,10 +255,10 @@ hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void*
     return hipErrorInvalidValue;
   const int rpb = affine_rows_per_block(rows, channels);
   const int blocks = (int)((rows + rpb - 1) / rpb);
-  const int per_pass = 256 / (channels >> 3);
-  const size_t lds = (size_t)per_pass * (channels >> 3) * 16 * sizeof(float);
-  hipLaunchKernelGGL(affine_relu_bwd_kernel, dim3(blocks), dim3(256), lds, s, (const uint16_t*)dout, (const uint16_t*)act, (const uint16_t*)y,
-                     (const uint16_t*)scale, (uint16_t*)dy, (uint16_t*)dsum, partial, rows, channels, rpb);
+  const int slab_chunks = affine_slab_chunks(channels);
+  const size_t lds = (size_t)(256 / slab_chunks) * slab_chunks * 16 * sizeof(float);
+  hipLaunchKernelGGL(affine_relu_bwd_kernel, dim3(blocks, affine_slabs(channels)), dim3(256), lds, s, (const uint16_t*)dout, (const uint16_t*)act,
+                     (const uint16_t*)y, (const uint16_t*)scale, (uint16_t*)dy, (uint16_t*)dsum, partial, rows, channels, rpb);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(reduce_pairs_kernel, dim3((2 * channels + 3) / 4), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
