@@ -111,5 +111,19 @@ __device__ __forceinline__ int xcd_tile(int block, int n_tiles) {
   return n_tiles % 8 == 0 ? (block & 7) * (n_tiles >> 3) + (block >> 3) : block;
 }
 
+// The same run of tiles per XCD, but walked in groups of kTileGroupM tile rows (down a group's rows first, then to
+// the next tile column), so that the tiles an XCD has in flight at one time form a compact block of the result:
+// they share few operand row panels, and the XCD's L2 fills stay near (rows + columns) instead of (all rows + 1).
+constexpr int kTileGroupM = 8;
+__device__ __forceinline__ void xcd_tile_grouped(int block, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  const int run = xcd_tile(block, tiles_m * tiles_n);
+  const int per_group = kTileGroupM * tiles_n;
+  const int group = run / per_group, r = run - group * per_group;
+  const int first_m = group * kTileGroupM;
+  const int gm = min(tiles_m - first_m, kTileGroupM);
+  tile_n = r / gm;
+  tile_m = first_m + (r - tile_n * gm);
+}
+
 }  // namespace gemm_detail
 }  // namespace spb

@@ -487,8 +487,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int tile = xcd_tile(blockIdx.x, p.tiles_m * p.tiles_n);
-  const int tile_m = tile % p.tiles_m, tile_n = tile / p.tiles_m;
+  int tile_m, tile_n;
+  xcd_tile_grouped(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
