@@ -5,8 +5,8 @@
  * forward pass to the loss, then backpropagate over a fixed suffix of the
  * network, starting at the output layer, and hand over the gradients of that
  * suffix only.  Layers below the cut get no input gradient, no weight gradient
- * and no saved activation (Sec. 1: "avoid storing intermediate outputs for
- * layers that are not going to participate in the backward pass").
+ * and no saved activation (Sec. 1: outputs of layers that take no part in the
+ * backward pass need not be kept).
  *
  * A model is an ordered list of units; the backward pass may stop only between
  * units.  L = number of units.  Depth k = number of units, counted from the
@@ -118,7 +118,7 @@ const char* spb_last_error(void);
 int spb_model_create(const spb_model_desc* desc, spb_model** out);
 int spb_model_destroy(spb_model* m);
 
-/* L, the number of units (Sec. 2: "a L layer DNN"; here the cut unit of the model). */
+/* L, the number of units (the layer count L of Sec. 2, counted in units, the granularity of the cut). */
 int spb_num_units(const spb_model* m, int32_t* n_units);
 
 /* Parameter list, unit order, input end first. */
@@ -136,8 +136,8 @@ int spb_bind_grads(spb_model* m, void* const* ptrs, int32_t n);
  * backward pass reads is kept (Sec. 1, Table 1's peak-memory column).  Errors: DEPTH_RANGE. */
 int spb_workspace_size(const spb_model* m, int32_t k, size_t* bytes);
 
-/* Full forward pass to the loss (Sec. 2: "performs a forward pass to obtain the loss with respect to
- * the model"), keeping only what a backward pass of depth <= stash_depth_k will read.
+/* Full forward pass to the loss (Sec. 2: every worker runs the whole forward pass), keeping only what a
+ * backward pass of depth <= stash_depth_k will read.
  *   x          device, model dtype: [batch, dims[0]] (MLP), NHWC images (CNN); int32 token ids [batch, seq]
  *              in [0, vocab) (encoder).  The encoder reads the ids again in a full-depth backward pass.
  *   labels     device, int32, one class index per loss row, each in [0, classes)
@@ -151,8 +151,8 @@ int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_
                 int32_t stash_depth_k, void* workspace, size_t workspace_bytes, float* loss_out,
                 void* stream);
 
-/* Backward pass over the top k units only (Sec. 2: "each worker performs backpropagation on a fixed
- * suffix of the network ... starting from the output layer").  Requires a preceding spb_forward with
+/* Backward pass over the top k units only (Sec. 2: a worker backpropagates a fixed suffix of the network
+ * that starts at the output layer).  Requires a preceding spb_forward with
  * stash_depth_k >= k on the same workspace.  Overwrites (does not accumulate into) the gradient
  * buffers of units >= L-k and touches no other gradient buffer; the lowest visited unit gets its
  * parameter gradients but no input gradient is formed for it.  k = 0 enqueues nothing.
@@ -160,15 +160,42 @@ int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_
  * not bound), HIP. */
 int spb_backward_truncated(spb_model* m, int32_t k, void* stream);
 
-/* The gradients a worker sends after a depth-k step (Sec. 2: "each worker sends the gradients
- * computed"): one view per parameter of the top k units, output end first, and nothing for the
+/* The gradients a worker sends after a depth-k step (Sec. 2: only the gradients it computed): one view per parameter of the top k units, output end first, and nothing for the
  * units below the cut.  out: host array of cap entries; n_out receives the count (0 for k = 0).
  * Errors: DEPTH_RANGE, INVALID_ARG (cap too small), STATE (gradients not bound). */
 int spb_grad_buffers(const spb_model* m, int32_t k, spb_grad_view* out, int32_t cap, int32_t* n_out);
 
 /* Fill with zeros the gradient buffers of the units below the cut, for callers that want dense
- * gradients ("absent or zero").  Buffers bound as NULL are skipped. */
+ * gradients.  Buffers bound as NULL are skipped. */
 int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream);
+
+/* Depth of worker j (1-based) among n_workers (Sec. 2: the j-th worker backpropagates jL/k of the layers,
+ * counted from the output; the paper does not say how the quotient is rounded: it is rounded up here, so
+ * that the last worker always runs the full backward pass).  Host-only; *k receives ceil(j * L / n_workers).
+ * Errors: INVALID_ARG (j outside 1..n_workers). */
+int spb_worker_depth(const spb_model* m, int32_t j, int32_t n_workers, int32_t* k);
+
+#define SPB_MAX_WORKERS 8
+
+/* Parameter-server side of one iteration (Sec. 2): the partial gradients of n_workers workers, worker j having
+ * backpropagated the top depths[j] units, are averaged per parameter over the workers that contributed to it
+ * (c = number of workers with depths[j] >= L - unit), the learning rate of a parameter is lr * c / n_workers when
+ * scale_lr is non-zero (Sec. 2 scales the rate with the number of contributors; the formula is this library's
+ * reading) and lr otherwise, and the parameter takes one step of SGD with momentum and weight decay (Sec. 4.1):
+ *     g = (1/c) * sum of the contributors' gradients;   v = momentum * v + g + weight_decay * w;   w = w - rate * v.
+ * A parameter no worker contributed to (c = 0) is left untouched, and so is its velocity.
+ *   depths        host array [n_workers], each in 0..L
+ *   worker_grads  host array [n_workers * n_params] of device pointers, entry j * n_params + i = worker j's
+ *                 float32 gradient of parameter i (dense, the parameter's shape); read only where worker j
+ *                 contributes to parameter i, may be NULL elsewhere
+ *   velocity      host array [n_params] of device pointers, float32, the parameter's shape, updated in place
+ * The parameters are the buffers bound with spb_bind_params (model dtype; a bfloat16 parameter is rounded to
+ * nearest-even after the float32 update) and are updated in place.  Enqueues on `stream`; allocates nothing.
+ * Errors: INVALID_ARG (n_workers outside 1..SPB_MAX_WORKERS, null pointers where one is read), DEPTH_RANGE,
+ * STATE (parameters not bound), HIP. */
+int spb_aggregate_update(spb_model* m, int32_t n_workers, const int32_t* depths, void* const* worker_grads,
+                         void* const* velocity, float lr, float momentum, float weight_decay, int32_t scale_lr,
+                         void* stream);
 
 /* Kernel timing.  When enabled, every kernel the model enqueues is bracketed by two HIP events on
  * the launch stream.  spb_read_kernel_timing waits for the recorded events, adds them up per kernel

@@ -2,8 +2,8 @@
 
 Each function is the textbook definition written out with one library matrix
 product per contraction; nothing is blocked, fused or reordered.  The paper
-treats the forward and backward passes as the usual ones (Sec. 1, "first a
-forward pass ... following this, a backward pass"); these are those passes.
+treats the forward and backward passes as the usual ones (Sec. 1: a forward
+pass to the loss, then a backward pass for the gradients); these are those passes.
 """
 from __future__ import annotations
 

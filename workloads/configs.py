@@ -7,7 +7,7 @@ and a bottleneck residual CNN, and a pre-LayerNorm Transformer encoder.  Only
 shapes live here.
 
 A model is a list of *units*; the backward pass may stop only between units
-(the paper's "fraction of the layers from the end", Sec. 1 and Sec. 2).
+(Sec. 1 and Sec. 2 speak of a fraction of the layers, counted from the end).
 Depth k counts units from the output end.
 """
 from __future__ import annotations

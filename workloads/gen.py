@@ -133,3 +133,17 @@ def make_batch(cfg: dict, seed: int = 0) -> dict:
         labels = _stream(seed, "batch/labels").integers(0, v, size=(rows,), dtype=np.int32)
         return {"x": torch.from_numpy(ids), "loss_rows": torch.from_numpy(perm), "labels": torch.from_numpy(labels)}
     raise NotImplementedError(fam)
+
+
+def make_worker_grads(cfg: dict, seed: int, n_workers: int) -> list:
+    """Stand-ins for the gradients of n_workers workers: one dict per worker, name -> float32 CPU tensor
+    N(0, 0.01^2) of the parameter's shape, for every parameter (which of them a worker of a given depth actually
+    sends is decided by whoever consumes them)."""
+    return [{name: torch.from_numpy(_normal(seed, f"worker{j}/{name}", shape, 0.01).astype(np.float32))
+             for name, shape, _unit, _init in tensor_specs(cfg)} for j in range(n_workers)]
+
+
+def make_velocity(cfg: dict, seed: int) -> dict:
+    """name -> float32 CPU tensor N(0, 0.01^2): the momentum buffers an optimizer would hold mid-training."""
+    return {name: torch.from_numpy(_normal(seed, "velocity/" + name, shape, 0.01).astype(np.float32))
+            for name, shape, _unit, _init in tensor_specs(cfg)}
