@@ -58,6 +58,35 @@ def measured_traffic(kernel_name):
     return rec
 
 
+def server_update(spb, torch, wl, model, cfg, n_workers=4, reps=50):
+    """The server side of an iteration (Sec. 2: per-layer average over the contributing workers, then the optimizer
+    step) for 4 workers at depths ceil(j L / 4), timed outside the step's timed region: an HBM-bound kernel, reported
+    as bytes it must move per second against the HBM peak."""
+    names = [i["name"] for i in model.infos]
+    depths = [spb.spb_worker_depth(model.handle, j, n_workers) for j in range(1, n_workers + 1)]
+    grads = [[torch.zeros_like(g) for g in model.grads] for _ in range(n_workers)]
+    vel = [torch.zeros_like(g) for g in model.grads]
+    es = 4 if cfg["dtype"] == "f32" else 2
+    nbytes = 0
+    for info in model.infos:
+        c = sum(1 for k in depths if info["unit"] >= model.n_units - k)
+        if c:
+            nbytes += info["numel"] * (4 * c + 8 + 2 * es)
+    stream = model.stream()
+    run = lambda: spb.spb_aggregate_update(model.handle, depths, grads, vel, 0.0, 0.9, 0.0, True, stream)   # rate 0: parameters stay as they are
+    for _ in range(5):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    return {"workers": n_workers, "depths": depths, "us": round(us, 2), "algorithmic_bytes": nbytes,
+            "gbps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / PEAK["hbm"], 4)}
+
+
 def cpu_baseline(cfg, params, batch, depths, budget_s):
     """The oracle as it stands, exact float64 mode, on this host's cores, on a bounded sample."""
     import oracle
@@ -231,6 +260,7 @@ def main():
         "roofline": roofline,
         "kernels": sorted(table, key=lambda r: -r["avg_us"] * r["launches_per_sweep"])[:16],
     }
+    out["server_update"] = server_update(spb, torch, wl, model, cfg)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, params, batch, depths, args.cpu_seconds)
     model.close()

@@ -63,6 +63,9 @@ EXPORTS = {
     "spb_backward_truncated": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "spb_grad_buffers": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spb_grad_view), C.c_int32, C.POINTER(C.c_int32)]),
     "spb_zero_absent_grads": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
+    "spb_worker_depth": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
+    "spb_aggregate_update": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                       C.c_float, C.c_float, C.c_float, C.c_int32, C.c_void_p]),
     "spb_set_kernel_timing": (C.c_int, [C.c_void_p, C.c_int32]),
     "spb_replay_kernel": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int32, C.c_void_p]),
     "spb_read_kernel_timing": (C.c_int, [C.c_void_p, C.POINTER(spb_kernel_time), C.c_int32, C.POINTER(C.c_int32)]),
@@ -197,6 +200,21 @@ def spb_grad_buffers(m, k, cap=None):
 
 def spb_zero_absent_grads(m, k, stream):
     _check(lib().spb_zero_absent_grads(m, k, C.c_void_p(stream)))
+
+
+def spb_worker_depth(m, j: int, n_workers: int) -> int:
+    k = C.c_int32()
+    _check(lib().spb_worker_depth(m, j, n_workers, C.byref(k)))
+    return k.value
+
+
+def spb_aggregate_update(m, depths, worker_grads, velocity, lr, momentum, weight_decay, scale_lr, stream):
+    """worker_grads: one list per worker, each with one tensor (or None) per parameter; velocity: one tensor per parameter."""
+    n = len(depths)
+    d = (C.c_int32 * n)(*depths)
+    flat = [g for per_worker in worker_grads for g in per_worker]
+    _check(lib().spb_aggregate_update(m, n, d, _ptr_array(flat), _ptr_array(velocity), lr, momentum, weight_decay,
+                                      int(bool(scale_lr)), C.c_void_p(stream)))
 
 
 def spb_set_kernel_timing(m, enable: bool):

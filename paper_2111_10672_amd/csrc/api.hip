@@ -288,6 +288,49 @@ int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream) {
   return SPB_OK;
 }
 
+int spb_worker_depth(const spb_model* m, int32_t j, int32_t n_workers, int32_t* k) {
+  SPB_REQUIRE(m && k, SPB_ERR_INVALID_ARG, "spb_worker_depth: null argument");
+  SPB_REQUIRE(n_workers >= 1 && j >= 1 && j <= n_workers, SPB_ERR_INVALID_ARG, "spb_worker_depth: worker %d outside 1..%d", j, n_workers);
+  const long long L = m->impl->num_units;
+  *k = (int32_t)((j * L + n_workers - 1) / n_workers);
+  return SPB_OK;
+}
+
+int spb_aggregate_update(spb_model* m, int32_t n_workers, const int32_t* depths, void* const* worker_grads,
+                         void* const* velocity, float lr, float momentum, float weight_decay, int32_t scale_lr,
+                         void* stream) {
+  SPB_REQUIRE(m && depths && worker_grads && velocity, SPB_ERR_INVALID_ARG, "spb_aggregate_update: null argument");
+  SPB_REQUIRE(n_workers >= 1 && n_workers <= SPB_MAX_WORKERS, SPB_ERR_INVALID_ARG, "spb_aggregate_update: %d workers outside 1..%d", n_workers, SPB_MAX_WORKERS);
+  static_assert(SPB_MAX_WORKERS == spb::kMaxAggWorkers, "worker limit");
+  auto& im = *m->impl;
+  for (int j = 0; j < n_workers; ++j)
+    if (int rc = depth_ok(m, depths[j], "spb_aggregate_update")) return rc;
+  SPB_REQUIRE(im.params_bound, SPB_ERR_STATE, "spb_aggregate_update: parameters not bound");
+  const int n_params = (int)im.params.size();
+  std::vector<spb::AggregateTensor> tensors;
+  for (int i = 0; i < n_params; ++i) {
+    spb::AggregateTensor t;
+    for (int j = 0; j < n_workers; ++j) {
+      if (im.params[i].unit < im.num_units - depths[j]) continue;  // worker j's suffix does not reach this unit
+      const void* g = worker_grads[(size_t)j * n_params + i];
+      SPB_REQUIRE(g && (reinterpret_cast<uintptr_t>(g) & 15) == 0, SPB_ERR_INVALID_ARG,
+                  "spb_aggregate_update: worker %d contributes to %s but its gradient pointer is null or not 16-byte aligned", j, im.params[i].name.c_str());
+      t.g[t.count++] = static_cast<const float*>(g);
+    }
+    if (t.count == 0) continue;  // nobody reached it: parameter and velocity stay as they are
+    SPB_REQUIRE(velocity[i] && (reinterpret_cast<uintptr_t>(velocity[i]) & 15) == 0 && im.param_ptrs[i], SPB_ERR_INVALID_ARG,
+                "spb_aggregate_update: velocity of %s null or not 16-byte aligned", im.params[i].name.c_str());
+    t.w = im.param_ptrs[i];
+    t.v = static_cast<float*>(velocity[i]);
+    t.numel = im.params[i].numel();
+    t.rate = scale_lr ? lr * (float)t.count / (float)n_workers : lr;
+    tensors.push_back(t);
+  }
+  hipError_t e = spb::launch_aggregate_update(tensors.data(), (int)tensors.size(), im.dtype, momentum, weight_decay, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) { set_error("spb_aggregate_update: %s", hipGetErrorString(e)); return SPB_ERR_HIP; }
+  return SPB_OK;
+}
+
 int spb_set_kernel_timing(spb_model* m, int32_t enable) {
   SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_set_kernel_timing: null model");
   m->impl->timer.enable(enable != 0);

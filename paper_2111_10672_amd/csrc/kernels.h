@@ -147,5 +147,20 @@ hipError_t launch_embedding_fwd(const int32_t* ids, const void* tok, const void*
 hipError_t launch_embedding_bwd(const int32_t* ids, const void* dx, int lddx, float* dtok, float* dpos, int batch, int seq, int vocab,
                                 int width, hipStream_t s);
 
+// Server-side aggregation and update (aggregate.hip): for each tensor, g = mean of `count` float32 worker
+// gradients (added in the order given), v = momentum * v + g + weight_decay * w, w = w - rate * v.  w is in
+// param_dtype (bfloat16 parameters are rounded to nearest-even after the float32 update), v is float32.
+constexpr int kMaxAggWorkers = 8;
+struct AggregateTensor {
+  void* w = nullptr;
+  float* v = nullptr;
+  const float* g[kMaxAggWorkers] = {};
+  long long numel = 0;
+  int count = 0;
+  float rate = 0.f;
+};
+hipError_t launch_aggregate_update(const AggregateTensor* tensors, int n_tensors, DType param_dtype, float momentum,
+                                   float weight_decay, hipStream_t stream);
+
 }  // namespace spb
 

@@ -95,3 +95,30 @@ def test_state_errors_without_a_gpu():
     finally:
         spb.spb_model_destroy(m)
     del cfg
+
+
+def test_worker_depth_rule_and_aggregation_argument_errors():
+    cfg = wl.get_config("cfg2")
+    m = spb.spb_model_create(spb.desc_from_config(cfg))
+    try:
+        L = wl.unit_count(cfg)
+        assert [spb.spb_worker_depth(m, j, 4) for j in range(1, 5)] == [2, 4, 6, 8]
+        assert [spb.spb_worker_depth(m, j, 3) for j in range(1, 4)] == [3, 6, 8]      # ceil(8 j / 3)
+        assert spb.spb_worker_depth(m, 5, 5) == L
+        for j, n in ((0, 4), (5, 4), (1, 0)):
+            with pytest.raises(spb.SpbError) as e:
+                spb.spb_worker_depth(m, j, n)
+            assert e.value.code == -1
+        n_params = spb.spb_param_count(m)
+        none = [None] * n_params
+        with pytest.raises(spb.SpbError) as e:      # too many workers
+            spb.spb_aggregate_update(m, [1] * 9, [none] * 9, none, 0.1, 0.9, 0.0, True, 0)
+        assert e.value.code == -1
+        with pytest.raises(spb.SpbError) as e:      # depth out of range
+            spb.spb_aggregate_update(m, [L + 1], [none], none, 0.1, 0.9, 0.0, True, 0)
+        assert e.value.code == -2
+        with pytest.raises(spb.SpbError) as e:      # parameters not bound
+            spb.spb_aggregate_update(m, [1], [none], none, 0.1, 0.9, 0.0, True, 0)
+        assert e.value.code == -3
+    finally:
+        spb.spb_model_destroy(m)
