@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--eager", action="store_true",
                     help="launch the timed steps eagerly instead of replaying HIP graphs (for counter collection, "
                          "which does not survive graph replay on this ROCm)")
+    ap.add_argument("--table1", action="store_true",
+                    help="print forward ms / backward ms / workspace GB against the percentage of units backpropagated, "
+                         "in the shape of the paper's Table 1 (ResNet-101-style stack, batch 64), and exit")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="run only a plain elementwise copy of this many MiB (10 launches) and exit: the reference "
                          "the HBM traffic counters are scaled by")
@@ -56,6 +59,38 @@ def measured_traffic(kernel_name):
     if rec.get("kernel") != kernel_name or rec.get("sources_sha256") != h.hexdigest():
         return None
     return rec
+
+
+def table1(spb, torch, wl, reps):
+    """Forward time, backward time and workspace against the share of units backpropagated, for the model and batch
+    size of the paper's Table 1 (its numbers are a V100's and another framework's: context, not a target).  Forward
+    time is `reps` forward passes between two events; backward time is the same for whole steps, minus that."""
+    cfg = wl.get_config("resnet101_cifar")
+    model = spb.SpbModel(cfg, wl.make_params(cfg, 0), "cuda:0")
+    dev = {n: t.cuda() for n, t in wl.make_batch(cfg, 0).items()}
+    L = model.n_units
+    rows = []
+    for pct in reversed(cfg["percents"]):
+        k = -(-pct * L // 100)
+        need = model.reserve(k)
+        model.step(dev, k)
+        torch.cuda.synchronize()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        e[0].record()
+        for _ in range(reps):
+            model.forward(dev, k)
+        e[1].record()
+        for _ in range(reps):
+            model.step(dev, k)
+        e[2].record()
+        torch.cuda.synchronize()
+        fwd, both = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+        rows.append({"percent": pct, "units": k, "forward_ms": round(fwd, 4), "backward_ms": round(both - fwd, 4),
+                     "workspace_gb": round(need / 1e9, 4)})
+    model.close()
+    print(json.dumps({"table": "forward / backward time and workspace vs share of units backpropagated",
+                      "workload": "resnet101_cifar: bottleneck stack [3,4,23,3], 32x32 images, batch 64, bf16",
+                      "units": L, "rows": rows}))
 
 
 def server_update(spb, torch, wl, model, cfg, n_workers=4, reps=50):
@@ -134,6 +169,10 @@ def main():
             torch.add(src, 0.0, out=dst)      # one read and one write of n bytes per launch
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 10}))
+        return
+
+    if args.table1:
+        table1(spb, torch, wl, max(3, min(args.steps, 20)))
         return
 
     cfg = wl.get_config(args.config)

@@ -47,3 +47,33 @@ def test_resnet_workspace_grows_with_depth():
     sizes = [spb.spb_workspace_size(m, k) for k in range(wl.unit_count(cfg) + 1)]
     spb.spb_model_destroy(m)
     assert all(b >= a for a, b in zip(sizes, sizes[1:])) and sizes[-1] > sizes[0]
+
+
+def test_resnet101_style_stack_at_table1_depths():
+    """The 35-unit stack of the Table-1-shaped report, at toy widths, at a few of its depths."""
+    cfg = wl.get_config("small_resnet101_bf16")
+    params, batch = wl.make_params(cfg, 0, True), wl.make_batch(cfg, 0)
+    n_units = wl.unit_count(cfg)
+    assert n_units == 35
+    _, exact = oracle.spb_step(cfg, params, batch, n_units)
+    ref_loss, ref = oracle.spb_step(cfg, params, batch, n_units, oracle.round_to_bf16)
+    unit_of = {n: u for n, _s, u, _i in wl.tensor_specs(cfg)}
+    model = spb.SpbModel(cfg, params)
+    try:
+        dev = {n: t.cuda() for n, t in batch.items()}
+        for k in wl.depth_sweep(cfg):
+            print(f"case small_resnet101_bf16 k={k}", flush=True)
+            for g in model.grads:
+                g.fill_(float("nan"))
+            model.step(dev, k)
+            torch.cuda.synchronize()
+            assert abs(model.loss.item() - ref_loss) <= 5e-3 * abs(ref_loss)
+            gpu = {n: g.double().cpu().numpy() for n, g in model.grad_dict(k).items()}
+            want = {n for n, u in unit_of.items() if u >= n_units - k}
+            assert set(gpu) == want
+            check_gradients(gpu, {n: ref[n] for n in want}, "bf16", {n: exact[n] for n in want})
+            for info, g in zip(model.infos, model.grads):
+                if info["unit"] < n_units - k:
+                    assert torch.isnan(g).all(), f"{info['name']} was written below the cut"
+    finally:
+        model.close()

@@ -35,6 +35,13 @@ CONFIGS = {
     "cfg5": dict(family="encoder", dtype="bf16", batch=32, seq=128, layers=12,
                  hidden=768, heads=12, ffn=3072, vocab=30522, loss_rows=614,
                  depths=[4, 7, 13]),
+    # ResNet-101-style stack on CIFAR-size images at batch 64 (the model and batch of Table 1); units = stem | 33
+    # bottlenecks | head.  Depths are the table's percentages of the 35 units, rounded up.
+    "resnet101_cifar": dict(family="resnet_bottleneck", dtype="bf16", batch=64,
+                            image=[32, 32, 3], stem=dict(kernel=3, stride=1, pad=1, pool=False, width=64),
+                            stage_blocks=[3, 4, 23, 3], stage_widths=[256, 512, 1024, 2048],
+                            classes=10, depths=[2, 4, 7, 11, 14, 18, 21, 25, 28, 32, 35],
+                            percents=[5, 10, 20, 30, 40, 50, 60, 70, 80, 90, 100]),
     # Small relatives used by the CPU tests and the small parity cases.
     "tiny_mlp_f32": dict(family="mlp", dtype="f32", batch=5,
                          dims=[12, 8, 8, 4], depths=[0, 1, 2, 3]),
@@ -58,6 +65,11 @@ CONFIGS = {
     "small_resnet_bottleneck_bf16": dict(family="resnet_bottleneck", dtype="bf16", batch=2, image=[20, 20, 3],
                                          stem=dict(kernel=7, stride=2, pad=3, pool=True, width=16),
                                          stage_blocks=[2, 1], stage_widths=[32, 64], classes=11, depths=[0, 1, 2, 3, 4, 5]),
+    # the 35-unit stack of resnet101_cifar at toy widths
+    "small_resnet101_bf16": dict(family="resnet_bottleneck", dtype="bf16", batch=2, image=[8, 8, 3],
+                                 stem=dict(kernel=3, stride=1, pad=1, pool=False, width=16),
+                                 stage_blocks=[3, 4, 23, 3], stage_widths=[32, 64, 128, 256], classes=5,
+                                 depths=[0, 2, 7, 18, 35]),
     "one_layer_bf16": dict(family="mlp", dtype="bf16", batch=16,
                            dims=[64, 10], depths=[0, 1]),
 }
