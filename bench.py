@@ -37,6 +37,12 @@ def parse():
     ap.add_argument("--table1", action="store_true",
                     help="print forward ms / backward ms / workspace GB against the percentage of units backpropagated, "
                          "in the shape of the paper's Table 1 (ResNet-101-style stack, batch 64), and exit")
+    ap.add_argument("--emulate", type=int, default=0, metavar="K",
+                    help="emulate one iteration of K workers time-multiplexed on this GPU (worker j backpropagates "
+                         "ceil(j L / K) units, then the server-side update), against K complete workers, and exit")
+    ap.add_argument("--round-robin", action="store_true",
+                    help="keep all five configurations resident and run their steps in turn: cost of switching between "
+                         "models whose parameters stay on the device, and exit")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="run only a plain elementwise copy of this many MiB (10 launches) and exit: the reference "
                          "the HBM traffic counters are scaled by")
@@ -91,6 +97,85 @@ def table1(spb, torch, wl, reps):
     print(json.dumps({"table": "forward / backward time and workspace vs share of units backpropagated",
                       "workload": "resnet101_cifar: bottleneck stack [3,4,23,3], 32x32 images, batch 64, bf16",
                       "units": L, "rows": rows}))
+
+
+def emulate(spb, torch, wl, name, n_workers, reps):
+    """One SPB iteration of K workers sharing this GPU in time (Sec. 2 and 3): each worker runs its step on its own
+    batch at its own depth into its own gradient buffers, then the server-side update consumes them.  The same with
+    K complete workers is ordinary data parallelism; the ratio is what SPB saves per iteration on one device."""
+    cfg = wl.get_config(name)
+    model = spb.SpbModel(cfg, wl.make_params(cfg, 0), "cuda:0")
+    L = model.n_units
+    batches = [{n: t.cuda() for n, t in wl.make_batch(cfg, 1 + j).items()} for j in range(n_workers)]
+    grads = [[torch.zeros_like(g) for g in model.grads] for _ in range(n_workers)]
+    vel = [torch.zeros_like(g) for g in model.grads]
+    model.reserve(L)
+
+    def iteration(depths):
+        for j, k in enumerate(depths):
+            spb.spb_bind_grads(model.handle, grads[j])
+            model.step(batches[j], k)
+        spb.spb_aggregate_update(model.handle, depths, grads, vel, 0.0, 0.9, 0.0, True, model.stream())   # rate 0: weights stay
+
+    out = {"workload": name, "workers": n_workers, "units": L, "batch_per_worker": cfg["batch"]}
+    for label, depths in (("spb", [spb.spb_worker_depth(model.handle, j, n_workers) for j in range(1, n_workers + 1)]),
+                          ("full", [L] * n_workers)):
+        for _ in range(3):
+            iteration(depths)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            iteration(depths)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[label] = {"depths": depths, "ms_per_iteration": round(ms, 4),
+                      "samples_per_s": round(n_workers * cfg["batch"] / (ms * 1e-3), 1)}
+    out["iteration_time_ratio_spb_over_full"] = round(out["spb"]["ms_per_iteration"] / out["full"]["ms_per_iteration"], 4)
+    model.close()
+    print(json.dumps(out))
+
+
+def round_robin(spb, torch, wl, reps):
+    """Sec. 3 keeps the parameters of several jobs on the device and switches between them; here the five
+    configurations stay resident (parameters, gradients, workspaces) and their steps run in turn at each one's
+    shallowest depth.  Reported: every model's step time alone and the time of a whole turn."""
+    names = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"]
+    models, batches, depths = [], [], []
+    for n in names:
+        cfg = wl.get_config(n)
+        m = spb.SpbModel(cfg, wl.make_params(cfg, 0), "cuda:0")
+        k = wl.depth_sweep(cfg)[0]
+        m.reserve(k)
+        models.append(m); depths.append(k)
+        batches.append({key: t.cuda() for key, t in wl.make_batch(cfg, 0).items()})
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    alone = [timed(lambda m=m, b=b, k=k: m.step(b, k)) for m, b, k in zip(models, batches, depths)]
+
+    def turn():
+        for m, b, k in zip(models, batches, depths):
+            m.step(b, k)
+
+    whole = timed(turn)
+    resident = sum(m.workspace_bytes + sum(p.numel() * p.element_size() + g.numel() * 4 for p, g in zip(m.params, m.grads)) for m in models)
+    for m in models:
+        m.close()
+    print(json.dumps({"models": names, "depths": depths, "step_ms_alone": [round(a, 4) for a in alone],
+                      "sum_alone_ms": round(sum(alone), 4), "turn_ms": round(whole, 4),
+                      "switching_overhead_ms": round(whole - sum(alone), 4), "resident_gb": round(resident / 1e9, 3)}))
 
 
 def server_update(spb, torch, wl, model, cfg, n_workers=4, reps=50):
@@ -173,6 +258,12 @@ def main():
 
     if args.table1:
         table1(spb, torch, wl, max(3, min(args.steps, 20)))
+        return
+    if args.emulate:
+        emulate(spb, torch, wl, args.config, args.emulate, max(5, min(args.steps, 200)))
+        return
+    if args.round_robin:
+        round_robin(spb, torch, wl, max(3, min(args.steps, 50)))
         return
 
     cfg = wl.get_config(args.config)

@@ -77,3 +77,38 @@ def test_cfg2_four_workers_at_the_paper_depth_rule():
 def test_some_parameters_unreached_and_eight_workers():
     _run("small_encoder_bf16", [0, 1, 1, 2, 2, 3, 3, 3], True)   # unit 0 (embedding) is below every cut
     _run("small_resnet_basic_bf16", [2, 3], False)
+
+
+def test_emulated_iteration_of_three_workers_end_to_end():
+    """Three workers' truncated steps on the GPU (own batches, depths ceil(j L / 3), own gradient buffers), then the
+    server-side update, against the same iteration done by the oracle throughout."""
+    cfg = wl.get_config("ragged_mlp_f32")
+    params = wl.make_params(cfg, 0, perturbed=True)
+    model = spb.SpbModel(cfg, params, "cuda:0")
+    names = [i["name"] for i in model.infos]
+    units = {i["name"]: i["unit"] for i in model.infos}
+    L, K, lr, mu, wd = model.n_units, 3, 0.05, 0.9, 1e-4
+    depths = [spb.spb_worker_depth(model.handle, j, K) for j in range(1, K + 1)]
+    assert depths == oracle.worker_depths(L, K) == [2, 3, 4]
+    vel = wl.make_velocity(cfg, 0)
+    dev_vel = [vel[n].cuda() for n in names]
+    batches = [wl.make_batch(cfg, 10 + j) for j in range(K)]
+    worker_bufs = [[torch.full_like(g, float("nan")) for g in model.grads] for _ in range(K)]
+    for j, k in enumerate(depths):
+        spb.spb_bind_grads(model.handle, worker_bufs[j])
+        model.step({n: t.cuda() for n, t in batches[j].items()}, k)
+    spb.spb_aggregate_update(model.handle, depths, worker_bufs, dev_vel, lr, mu, wd, True, model.stream())
+    torch.cuda.synchronize()
+    ref_grads = [oracle.spb_step(cfg, params, batches[j], k)[1] for j, k in enumerate(depths)]
+    old = {n: params[n].double().numpy() for n in names}
+    ref_w, ref_v = oracle.aggregate_update(units, L, old, {n: vel[n].double().numpy() for n in names}, ref_grads, depths, lr, mu, wd, True)
+    for i, n in enumerate(names):
+        step_ref = ref_w[n] - old[n]
+        step_gpu = model.params[i].double().cpu().numpy() - old[n]
+        if not np.any(step_ref):
+            assert not np.any(step_gpu), n
+            continue
+        # the step is a few 1e-3 of a weight stored in float32: its own rounding (6e-8 of the weight) sets the floor
+        assert np.abs(step_gpu - step_ref).max() <= 1e-4 * np.abs(step_ref).max() + 2e-7 * np.abs(old[n]).max(), n
+        np.testing.assert_allclose(dev_vel[i].double().cpu().numpy(), ref_v[n], rtol=0, atol=1e-4 * np.abs(ref_v[n]).max(), err_msg=n)
+    model.close()
