@@ -1,0 +1,171 @@
+// Attention of one (batch entry, head) in one workgroup: S = Q K^T / sqrt(d), P = softmax over keys, ctx = P V, for
+// sequences of at most 128 positions and heads of 64 features (the encoder configuration).  The unfused path
+// writes the float32 scores to HBM, reads them back for the softmax, writes P and reads it back for the second
+// product; here Q, K and V are fetched once into LDS, the scores never leave the accumulators, and P goes to HBM
+// only when the backward pass will read it (it is the stash of the unit, in bfloat16, and the same bfloat16
+// values feed the second product, as in the unfused path).
+//
+// Four waves, each owning 32 query rows from start to end: after the one barrier that publishes the tiles no wave
+// waits for another.  Row-wise maximum and sum run over the accumulator layout (a row lives in the 32 lanes of one
+// half-wave, 4 tiles wide), P is parked per wave in LDS in the layout the second product's A fragments read.
+#include "gemm_dma_impl.h"
+
+namespace spb {
+namespace {
+using namespace gemm_dma_detail;
+
+constexpr int kSeqMax = 128, kHeadDim = 64;
+constexpr int kQBytes = kSeqMax * kRowBytes;          // Q tile, RowK: 128 rows x 64 features
+constexpr int kVBytes = 2 * kHeadDim * kRowBytes;     // V, KRow: two k tiles (64 keys each) x 64 feature rows
+constexpr int kPWave = 2 * 32 * kRowBytes;            // one wave's P: two k tiles (64 keys each) x 32 query rows
+constexpr int kAttnLds = 2 * kQBytes + kVBytes + 4 * kPWave;
+
+__global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __restrict__ qkv, int ld_qkv, bf16_t* __restrict__ prob,
+                                                            bf16_t* __restrict__ ctx, int ld_ctx, int heads, int seq, float scale) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* q_tile = lds;
+  char* k_tile = lds + kQBytes;
+  char* v_tile = lds + 2 * kQBytes;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* p_tile = lds + 2 * kQBytes + kVBytes + wave * kPWave;
+  const int z = blockIdx.x, b = z / heads, h = z - b * heads;
+  const int hidden = heads * kHeadDim;
+  const bf16_t* base = qkv + (size_t)b * seq * ld_qkv + h * kHeadDim;
+  ConvGeom none{};
+
+  TileSource<kSeqMax, Layout::RowK, Gather::None, 4> src_q, src_k;
+  TileSource<kHeadDim, Layout::KRow, Gather::None, 4> src_v;
+  src_q.init(base, ld_qkv, 0, seq, wave, lane, 0, none);
+  src_k.init(base + hidden, ld_qkv, 0, seq, wave, lane, 0, none);
+  src_v.init(base + 2 * hidden, ld_qkv, 0, kHeadDim, wave, lane, 0, none);
+  src_q.issue(0, kHeadDim, q_tile, wave, ld_qkv, none);
+  src_k.issue(0, kHeadDim, k_tile, wave, ld_qkv, none);
+  src_v.issue(0, seq, v_tile, wave, ld_qkv, none);
+  src_v.issue(1, seq, v_tile + kHeadDim * kRowBytes, wave, ld_qkv, none);
+  wait_loads_and_barrier<0>();
+
+  // scores of this wave's 32 queries against all keys
+  f32x16 s[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[j][r] = 0.f;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const u32x4 a = read_fragment<kSeqMax, Layout::RowK>(q_tile, 32 * wave, g, lane);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x4 kb = read_fragment<kSeqMax, Layout::RowK>(k_tile, 32 * j, g, lane);
+      s[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, kb), s[j], 0, 0, 0);
+    }
+  }
+  // softmax over the keys of each row: accumulator register r of tile j holds (row 8 (r / 4) + 4 (lane / 32) + r % 4,
+  // key 32 j + lane % 32), so a row is spread over the 32 lanes of a half-wave
+  const int key0 = lane & 31;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      s[j][r] = 32 * j + key0 < seq ? s[j][r] * scale : -INFINITY;
+      m = fmaxf(m, s[j][r]);
+    }
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { s[j][r] = expf(s[j][r] - m); sum += s[j][r]; }
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    const float inv = 1.f / sum;
+    const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int key = 32 * j + key0;                    // k tile key / 64, chunk (key % 64) / 8, element key % 8
+      bf16_t v;
+      store_elem(&v, s[j][r] * inv);
+      *reinterpret_cast<bf16_t*>(p_tile + (key >> 6) * (32 * kRowBytes) + lds_offset(row, (key & 63) >> 3) + (key & 7) * 2) = v;
+    }
+  }
+  asm volatile("" ::: "memory");  // the parked P is read back through pointers of another type
+  // ctx = P V with the parked bfloat16 P as A and the transposing reads of V as B
+  f32x16 o[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x4 a[1], vb[2];
+      a[0] = read_fragment<32, Layout::RowK>(p_tile + kt * (32 * kRowBytes), 0, g, lane);
+      vb[0] = read_fragment<kHeadDim, Layout::KRow>(v_tile + kt * (kHeadDim * kRowBytes), 0, g, lane);
+      vb[1] = read_fragment<kHeadDim, Layout::KRow>(v_tile + kt * (kHeadDim * kRowBytes), 32, g, lane);
+      fragments_ready(a, vb);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        o[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[0]), __builtin_bit_cast(bf16x8, vb[j]), o[j], 0, 0, 0);
+    }
+  }
+  // P to HBM (only when it is kept): 16-byte chunks from the parked tiles; LDS operations of a wave run in order
+  const int q0 = 32 * wave;
+  if (prob) {
+    bf16_t* dst = prob + (size_t)z * seq * seq;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int idx = it * 64 + lane, row = idx >> 4, chunk = idx & 15;   // 32 rows x 16 chunks of 8 keys
+      if (q0 + row < seq && chunk * 8 < seq) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(p_tile + (chunk >> 3) * (32 * kRowBytes) + lds_offset(row, chunk & 7));
+        *reinterpret_cast<u32x4*>(dst + (size_t)(q0 + row) * seq + chunk * 8) = v;
+      }
+    }
+  }
+  asm volatile("" ::: "memory");
+  // ctx through the same LDS region (P is dead once its fragments and its copy are read): 32 rows x 64 floats
+  float* stage = reinterpret_cast<float*>(p_tile);
+  constexpr int kPitch = kHeadDim;  // no padding: the region is exactly 32 x 64 floats
+  static_assert(32 * kPitch * 4 <= kPWave, "ctx staging fits in the wave's P region");
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + 32 * j + (lane & 31)] = o[j][r];
+  asm volatile("" ::: "memory");
+  bf16_t* out = ctx + (size_t)b * seq * ld_ctx + h * kHeadDim;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = it * 8 + (lane >> 3), c = (lane & 7) * 8;
+    if (q0 + row < seq) {
+      float v[8];
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c), v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
+      *reinterpret_cast<u32x4*>(out + (size_t)(q0 + row) * ld_ctx + c) = pack_bf16x8(v);
+    }
+  }
+}
+
+}  // namespace
+
+bool attention_fused_accepts(int seq, int head_dim, int ld_qkv, int ld_ctx) {
+  return head_dim == kHeadDim && seq >= 1 && seq <= kSeqMax && seq % 8 == 0 && ld_qkv % 8 == 0 && ld_ctx % 8 == 0;
+}
+
+hipError_t launch_attention_fwd(const void* qkv, int ld_qkv, void* prob, void* ctx, int ld_ctx, int batch, int heads, int seq,
+                                int head_dim, float scale, hipStream_t stream) {
+  if (!qkv || !ctx || batch <= 0 || heads <= 0 || !attention_fused_accepts(seq, head_dim, ld_qkv, ld_ctx)) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(ctx) | reinterpret_cast<uintptr_t>(prob)) & 15) return hipErrorInvalidValue;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(attention_fwd_kernel, dim3(batch * heads), dim3(256), kAttnLds, stream, static_cast<const bf16_t*>(qkv), ld_qkv,
+                     static_cast<bf16_t*>(prob), static_cast<bf16_t*>(ctx), ld_ctx, heads, seq, scale);
+  return hipGetLastError();
+}
+
+}  // namespace spb

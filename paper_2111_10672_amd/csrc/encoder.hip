@@ -143,6 +143,12 @@ class EncoderModel : public Model {
       if (int rc = run("layernorm_fwd", 2 * mh, s, [&] {
             return launch_layernorm_fwd(xin, H, nullptr, M, H, P(LN1W), P(LN1B), w + b.u, H, reinterpret_cast<float*>(w + b.stats1), s); })) return rc;
       if (int rc = gemm(linear(w + b.u, H, M, P(QKVW), 3 * H, H, P(QKVB), w + b.qkv, 3 * H), s)) return rc;
+      if (attention_fused_accepts(S, D, 3 * H, H)) {
+        // one kernel per layer; P is written only where the backward pass will read it
+        void* keep_prob = (i + 1 >= num_units - k) ? w + b.prob : nullptr;
+        if (int rc = run("attention_fwd", (double)M * H * 2 * 4 + (keep_prob ? (double)Z * S * S * 2 : 0.0), s, [&] {
+              return launch_attention_fwd(w + b.qkv, 3 * H, keep_prob, w + b.ctx, H, B, NH, S, D, inv_sqrt_d, s); })) return rc;
+      } else {
       {
         GemmProblem g;  // scores[z, s, s'] = Q[s, :] . K[s', :] / sqrt(d)
         g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::RowK; g.epilogue = Epilogue::StoreF32;
@@ -162,6 +168,7 @@ class EncoderModel : public Model {
         g.batch = Z; g.a_batch = per_matrix(); g.b_batch = per_head(3 * H); g.c_batch = per_head(H);
         g.name = "attn_context";
         if (int rc = gemm(g, s)) return rc;
+      }
       }
       {
         GemmProblem g = linear(w + b.ctx, H, M, P(OUTW), H, H, P(OUTB), w + b.h, H);

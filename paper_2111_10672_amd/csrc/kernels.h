@@ -147,6 +147,13 @@ hipError_t launch_embedding_fwd(const int32_t* ids, const void* tok, const void*
 hipError_t launch_embedding_bwd(const int32_t* ids, const void* dx, int lddx, float* dtok, float* dpos, int batch, int seq, int vocab,
                                 int width, hipStream_t s);
 
+// Fused attention forward (attention.hip): per (batch entry, head), ctx = softmax(Q K^T * scale) V with Q, K, V the
+// three column blocks of qkv [batch * seq, 3 * heads * head_dim]; prob [batch * heads, seq, seq] (bfloat16) is
+// written only when non-null.  attention_fused_accepts says which shapes it takes (head_dim 64, seq <= 128, ...).
+bool attention_fused_accepts(int seq, int head_dim, int ld_qkv, int ld_ctx);
+hipError_t launch_attention_fwd(const void* qkv, int ld_qkv, void* prob, void* ctx, int ld_ctx, int batch, int heads, int seq,
+                                int head_dim, float scale, hipStream_t stream);
+
 // Server-side aggregation and update (aggregate.hip): for each tensor, g = mean of `count` float32 worker
 // gradients (added in the order given), v = momentum * v + g + weight_decay * w, w = w - rate * v.  w is in
 // param_dtype (bfloat16 parameters are rounded to nearest-even after the float32 update), v is float32.

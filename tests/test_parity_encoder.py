@@ -24,16 +24,17 @@ def _step(cfg, params, batch, k):
     return model
 
 
+@pytest.mark.parametrize("name", ["small_encoder_bf16", "fused_attention_encoder_bf16", "fused_attention_short_bf16"])
 @pytest.mark.parametrize("perturbed", [True, False])
-def test_small_encoder_every_depth(perturbed):
-    cfg = wl.get_config("small_encoder_bf16")
+def test_small_encoder_every_depth(perturbed, name):
+    cfg = wl.get_config(name)
     params, batch = wl.make_params(cfg, 0, perturbed), wl.make_batch(cfg, 0)
     n_units = wl.unit_count(cfg)
     exact_loss, exact = oracle.spb_step(cfg, params, batch, n_units)
     ref_loss, ref = oracle.spb_step(cfg, params, batch, n_units, oracle.round_to_bf16)
     unit_of = {n: u for n, _s, u, _i in wl.tensor_specs(cfg)}
     for k in range(n_units + 1):
-        print(f"case small_encoder_bf16 perturbed={perturbed} k={k}", flush=True)
+        print(f"case {name} perturbed={perturbed} k={k}", flush=True)
         model = _step(cfg, params, batch, k)
         try:
             assert abs(model.loss.item() - ref_loss) <= 5e-3 * abs(ref_loss)

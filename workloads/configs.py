@@ -53,6 +53,11 @@ CONFIGS = {
                          vocab=11, loss_rows=3, depths=[0, 1, 2, 3, 4]),
     "small_encoder_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=2, hidden=64, heads=4,
                                ffn=136, vocab=203, loss_rows=17, depths=[0, 1, 2, 3, 4]),
+    # heads of 64 features and sequences of at most 128 positions take the fused attention kernel
+    "fused_attention_encoder_bf16": dict(family="encoder", dtype="bf16", batch=2, seq=128, layers=2, hidden=128, heads=2,
+                                         ffn=256, vocab=97, loss_rows=31, depths=[0, 1, 2, 3, 4]),
+    "fused_attention_short_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=1, hidden=64, heads=1,
+                                       ffn=128, vocab=53, loss_rows=11, depths=[0, 1, 2, 3]),
     "tiny_resnet_basic": dict(family="resnet_basic", dtype="bf16", batch=2, image=[6, 6, 3],
                               stem=dict(kernel=3, stride=1, pad=1, pool=False, width=4),
                               stage_blocks=[1, 1], stage_widths=[4, 6], classes=3, depths=[0, 1, 2, 3, 4]),
