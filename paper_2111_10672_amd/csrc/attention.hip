@@ -147,6 +147,195 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
   }
 }
 
+
+// Backward of the same attention, one workgroup per (batch entry, head):
+//   dP = dctx V^T;  dS = P * (dP - rowsum(dP * P)) * scale (rounded to bfloat16, as the unfused path stores it);
+//   dQ = dS K;  dK = dS^T Q;  dV = P^T dctx.
+// Phase 1 is row-wise: wave w forms dP and dS of its 32 queries in the accumulator layout (P comes straight from
+// HBM in that layout) and parks dS twice, as the RowK tiles its own dQ product reads and into a workgroup-wide KRow
+// tile (k = query) that dK reads.  After one barrier, phase 2: wave w produces rows 32 w .. of dQ, dK and dV, three
+// products of 16 MFMAs each, with K, Q and dctx read through transposing LDS reads and P as a KRow tile that came
+// in by direct-to-LDS loads.  LDS: dctx twice (RowK for dP, KRow for dV), V (RowK), K, Q (KRow), P (KRow) and
+// the two dS copies; the KRow dS tile takes over the space of dctx-RowK and V once dP is done.
+constexpr int kDsK = kSeqMax * 2 * kSeqMax;  // dS as KRow tiles: two k tiles of 64 queries x 128 key rows
+constexpr int kBwdLds = kQBytes /*dctx RowK*/ + kQBytes /*V RowK*/ + 3 * kVBytes /*dctx, K, Q as KRow*/ + kDsK /*P KRow*/ + 4 * kPWave;
+static_assert(2 * kQBytes == kDsK, "the KRow dS tile reuses the dctx and V tiles of phase 1");
+
+__global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __restrict__ qkv, int ld_qkv, const bf16_t* __restrict__ prob,
+                                                            const bf16_t* __restrict__ dctx, int ld_ctx, bf16_t* __restrict__ dqkv,
+                                                            int heads, int seq, float scale) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* dctx_r = lds;                           // phase 1; then, with v_r, the KRow dS tile
+  char* v_r = lds + kQBytes;
+  char* ds_k = lds;
+  char* dctx_k = lds + 2 * kQBytes;
+  char* k_k = dctx_k + kVBytes;
+  char* q_k = k_k + kVBytes;
+  char* p_k = q_k + kVBytes;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* ds_r = p_k + kDsK + wave * kPWave;      // this wave's dS as RowK tiles (two k tiles of 64 keys x 32 rows)
+  const int z = blockIdx.x, b = z / heads, h = z - b * heads;
+  const int hidden = heads * kHeadDim;
+  const bf16_t* base = qkv + (size_t)b * seq * ld_qkv + h * kHeadDim;
+  const bf16_t* dc = dctx + (size_t)b * seq * ld_ctx + h * kHeadDim;
+  const bf16_t* pz = prob + (size_t)z * seq * seq;
+  ConvGeom none{};
+
+  {
+    TileSource<kSeqMax, Layout::RowK, Gather::None, 4> src_dc, src_v;
+    TileSource<kHeadDim, Layout::KRow, Gather::None, 4> src_dck, src_k, src_q;
+    TileSource<kSeqMax, Layout::KRow, Gather::None, 4> src_p;
+    src_dc.init(dc, ld_ctx, 0, seq, wave, lane, 0, none);
+    src_v.init(base + 2 * hidden, ld_qkv, 0, seq, wave, lane, 0, none);
+    src_dck.init(dc, ld_ctx, 0, kHeadDim, wave, lane, 0, none);
+    src_k.init(base + hidden, ld_qkv, 0, kHeadDim, wave, lane, 0, none);
+    src_q.init(base, ld_qkv, 0, kHeadDim, wave, lane, 0, none);
+    src_p.init(pz, seq, 0, seq, wave, lane, 0, none);
+    src_dc.issue(0, kHeadDim, dctx_r, wave, ld_ctx, none);
+    src_v.issue(0, kHeadDim, v_r, wave, ld_qkv, none);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      src_dck.issue(t, seq, dctx_k + t * (kHeadDim * kRowBytes), wave, ld_ctx, none);
+      src_k.issue(t, seq, k_k + t * (kHeadDim * kRowBytes), wave, ld_qkv, none);
+      src_q.issue(t, seq, q_k + t * (kHeadDim * kRowBytes), wave, ld_qkv, none);
+      src_p.issue(t, seq, p_k + t * (kSeqMax * kRowBytes), wave, seq, none);
+    }
+  }
+  // P of this wave's rows in the accumulator layout, straight from HBM, while the tiles are in flight
+  const int key0 = lane & 31, q0 = 32 * wave;
+  float pv[4][16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int q = q0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int key = 32 * j + key0;
+      pv[j][r] = (q < seq && key < seq) ? to_float(pz[(size_t)q * seq + key]) : 0.f;
+    }
+  }
+  wait_loads_and_barrier<0>();
+
+  // phase 1: dP = dctx V^T for this wave's queries
+  f32x16 dp[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dp[j][r] = 0.f;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const u32x4 a = read_fragment<kSeqMax, Layout::RowK>(dctx_r, q0, g, lane);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x4 vb = read_fragment<kSeqMax, Layout::RowK>(v_r, 32 * j, g, lane);
+      dp[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, vb), dp[j], 0, 0, 0);
+    }
+  }
+  // dS, rounded to bfloat16, kept in registers until every wave is done with the phase-1 tiles
+  uint16_t ds_bits[4][16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float dot = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dot += dp[j][r] * pv[j][r];
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      bf16_t v;
+      store_elem(&v, pv[j][r] * (dp[j][r] - dot) * scale);
+      ds_bits[j][r] = v.bits;
+    }
+  }
+  __syncthreads();  // all waves have read dctx_r and v_r: their space becomes the KRow dS tile
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);   // query within the wave
+    const int q = q0 + row;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int key = 32 * j + key0;
+      // RowK copy (rows = this wave's queries, k = key)
+      *reinterpret_cast<uint16_t*>(ds_r + (key >> 6) * (32 * kRowBytes) + lds_offset(row, (key & 63) >> 3) + (key & 7) * 2) = ds_bits[j][r];
+      // KRow copy (k = query, rows = keys): k tile q / 64, k-row q % 64, 128 rows of 2 bytes with the tile's chunk rotation
+      const int kk = q & 63;
+      const int pc = ((key >> 3) + krow_rot<kSeqMax>(kk)) & (kSeqMax / 8 - 1);
+      *reinterpret_cast<uint16_t*>(ds_k + (q >> 6) * (kSeqMax * kRowBytes) + kk * (kSeqMax * 2) + pc * 16 + (key & 7) * 2) = ds_bits[j][r];
+    }
+  }
+  __syncthreads();
+
+  // phase 2: three [32 x 64] outputs per wave; each goes out through the wave's own staging rows
+  float* stage = reinterpret_cast<float*>(ds_r);   // reused after dQ has read ds_r (LDS operations of a wave run in order)
+  constexpr int kPitch = kHeadDim;
+  auto write_out = [&](f32x16 (&o)[2], int col_block) {
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + 32 * j + (lane & 31)] = o[j][r];
+    asm volatile("" ::: "memory");
+    bf16_t* out = dqkv + (size_t)b * seq * ld_qkv + col_block * hidden + h * kHeadDim;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int row = it * 8 + (lane >> 3), c = (lane & 7) * 8;
+      if (q0 + row < seq) {
+        float v[8];
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c), v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
+        *reinterpret_cast<u32x4*>(out + (size_t)(q0 + row) * ld_qkv + c) = pack_bf16x8(v);
+      }
+    }
+    asm volatile("" ::: "memory");
+  };
+  auto zero = [](f32x16 (&o)[2]) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
+  };
+  f32x16 acc[2];
+  // dQ[q, d] = sum_key dS[q, key] K[key, d]
+  zero(acc);
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x4 a[1], bb[2];
+      a[0] = read_fragment<32, Layout::RowK>(ds_r + kt * (32 * kRowBytes), 0, g, lane);
+      bb[0] = read_fragment<kHeadDim, Layout::KRow>(k_k + kt * (kHeadDim * kRowBytes), 0, g, lane);
+      bb[1] = read_fragment<kHeadDim, Layout::KRow>(k_k + kt * (kHeadDim * kRowBytes), 32, g, lane);
+      fragments_ready(a, bb);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[0]), __builtin_bit_cast(bf16x8, bb[j]), acc[j], 0, 0, 0);
+    }
+  write_out(acc, 0);
+  // dK[key, d] = sum_q dS[q, key] Q[q, d]   and   dV[key, d] = sum_q P[q, key] dctx[q, d]: rows = this wave's 32 keys
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    const char* a_tile = which == 0 ? ds_k : p_k;
+    const char* b_tile = which == 0 ? q_k : dctx_k;
+    zero(acc);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x4 a[1], bb[2];
+        a[0] = read_fragment<kSeqMax, Layout::KRow>(a_tile + kt * (kSeqMax * kRowBytes), q0, g, lane);
+        bb[0] = read_fragment<kHeadDim, Layout::KRow>(b_tile + kt * (kHeadDim * kRowBytes), 0, g, lane);
+        bb[1] = read_fragment<kHeadDim, Layout::KRow>(b_tile + kt * (kHeadDim * kRowBytes), 32, g, lane);
+        fragments_ready(a, bb);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[0]), __builtin_bit_cast(bf16x8, bb[j]), acc[j], 0, 0, 0);
+      }
+    write_out(acc, 1 + which);
+  }
+}
+
 }  // namespace
 
 bool attention_fused_accepts(int seq, int head_dim, int ld_qkv, int ld_ctx) {
@@ -165,6 +354,22 @@ hipError_t launch_attention_fwd(const void* qkv, int ld_qkv, void* prob, void* c
   }
   hipLaunchKernelGGL(attention_fwd_kernel, dim3(batch * heads), dim3(256), kAttnLds, stream, static_cast<const bf16_t*>(qkv), ld_qkv,
                      static_cast<bf16_t*>(prob), static_cast<bf16_t*>(ctx), ld_ctx, heads, seq, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd(const void* qkv, int ld_qkv, const void* prob, const void* dctx, int ld_ctx, void* dqkv, int batch,
+                                int heads, int seq, int head_dim, float scale, hipStream_t stream) {
+  if (!qkv || !prob || !dctx || !dqkv || batch <= 0 || heads <= 0 || !attention_fused_accepts(seq, head_dim, ld_qkv, ld_ctx)) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(prob) | reinterpret_cast<uintptr_t>(dctx) | reinterpret_cast<uintptr_t>(dqkv)) & 15)
+    return hipErrorInvalidValue;
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLds);
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(attention_bwd_kernel, dim3(batch * heads), dim3(256), kBwdLds, stream, static_cast<const bf16_t*>(qkv), ld_qkv,
+                     static_cast<const bf16_t*>(prob), static_cast<const bf16_t*>(dctx), ld_ctx, static_cast<bf16_t*>(dqkv), heads, seq, scale);
   return hipGetLastError();
 }
 

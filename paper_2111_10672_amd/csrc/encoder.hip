@@ -248,6 +248,10 @@ class EncoderModel : public Model {
       if (int rc = gemm(wgrad(w + p.dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), s)) return rc;
       if (int rc = gemm(dgrad(w + p.dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
       const char* qbase = w + b.qkv;
+      if (attention_fused_accepts(S, D, 3 * H, H)) {
+        if (int rc = run("attention_bwd", (double)M * H * 2 * 7 + (double)Z * S * S * 2, s, [&] {
+              return launch_attention_bwd(qbase, 3 * H, w + b.prob, w + p.dctx, H, w + p.dqkv, B, NH, S, D, inv_sqrt_d, s); })) return rc;
+      } else {
       {
         GemmProblem g;  // dP[s, s'] = dctx[s, :] . V[s', :]
         g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::RowK; g.epilogue = Epilogue::StoreF32;
@@ -273,6 +277,7 @@ class EncoderModel : public Model {
       if (int rc = attn_out("attn_bwd_dv", Layout::KRow, w + b.prob, S, per_matrix(), w + p.dctx, 2)) return rc;
       if (int rc = attn_out("attn_bwd_dq", Layout::RowK, w + p.dscore, S, per_matrix(), bf(qbase, (size_t)H), 0)) return rc;
       if (int rc = attn_out("attn_bwd_dk", Layout::KRow, w + p.dscore, S, per_matrix(), qbase, 1)) return rc;
+      }
       if (int rc = gemm(wgrad(w + p.dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), s)) return rc;
       if (int rc = gemm(dgrad(w + p.dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
       void* dx = lowest ? nullptr : w + p.dx[which ^ 1];

@@ -154,6 +154,11 @@ bool attention_fused_accepts(int seq, int head_dim, int ld_qkv, int ld_ctx);
 hipError_t launch_attention_fwd(const void* qkv, int ld_qkv, void* prob, void* ctx, int ld_ctx, int batch, int heads, int seq,
                                 int head_dim, float scale, hipStream_t stream);
 
+// Its backward: dqkv [batch * seq, 3 * heads * head_dim] receives dQ, dK, dV from prob (as the forward wrote it),
+// qkv and dctx [batch * seq, heads * head_dim].
+hipError_t launch_attention_bwd(const void* qkv, int ld_qkv, const void* prob, const void* dctx, int ld_ctx, void* dqkv, int batch,
+                                int heads, int seq, int head_dim, float scale, hipStream_t stream);
+
 // Server-side aggregation and update (aggregate.hip): for each tensor, g = mean of `count` float32 worker
 // gradients (added in the order given), v = momentum * v + g + weight_decay * w, w = w - rate * v.  w is in
 // param_dtype (bfloat16 parameters are rounded to nearest-even after the float32 update), v is float32.
