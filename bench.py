@@ -6,7 +6,8 @@ paper) on one synthetic batch that is already resident in HBM.  The timed region
 depth of the workload's sweep in turn, a HIP graph that holds exactly the kernels the two C-ABI calls
 enqueue; `--steps` is the total number of timed steps, shared evenly between the depths.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, per-depth times, the roofline of the dominant kernel, the server-side
+update and the CPU rate of the oracle.  Other modes: --table1, --emulate K, --round-robin (each prints one line too).
 """
 from __future__ import annotations
 

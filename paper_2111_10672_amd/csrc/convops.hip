@@ -181,6 +181,44 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const uint16_t* __rest
   if (which) which[idx] = (uint8_t)arg;
 }
 
+// The same, eight channels (16 bytes) per thread, for channel counts that are multiples of 8.
+__global__ __launch_bounds__(256) void maxpool_fwd8_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ out, uint8_t* __restrict__ which,
+                                                           int n, int h, int w, int c, int oh, int ow) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int c8 = c >> 3;
+  if (idx >= (long long)n * oh * ow * c8) return;
+  const int chunk = idx % c8;
+  long long t = idx / c8;
+  const int j = t % ow; t /= ow;
+  const int i = t % oh;
+  const int b = t / oh;
+  float best[8];
+  int arg[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { best[e] = -INFINITY; arg[e] = 0; }
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int s = 0; s < 3; ++s) {
+      const int hi = 2 * i + r - 1, wi = 2 * j + s - 1;
+      if ((unsigned)hi < (unsigned)h && (unsigned)wi < (unsigned)w) {
+        float v[8];
+        unpack8(*reinterpret_cast<const u32x4*>(x + ((size_t)(b * h + hi) * w + wi) * c + chunk * 8), v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (v[e] > best[e]) { best[e] = v[e]; arg[e] = r * 3 + s; }
+      }
+    }
+  const size_t o = (size_t)idx * 8;
+  *reinterpret_cast<u32x4*>(out + o) = pack8(best);
+  if (which) {
+    uint2 wbits;
+    wbits.x = arg[0] | (arg[1] << 8) | (arg[2] << 16) | (arg[3] << 24);
+    wbits.y = arg[4] | (arg[5] << 8) | (arg[6] << 16) | (arg[7] << 24);
+    *reinterpret_cast<uint2*>(which + o) = wbits;
+  }
+}
+
 // da[n, h, w, c] = sum of dout over the (at most 4) windows whose maximum sat at (h, w).
 __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const uint16_t* __restrict__ dout, const uint8_t* __restrict__ which,
                                                           uint16_t* __restrict__ da, int n, int h, int w, int c, int oh, int ow) {
@@ -281,6 +319,11 @@ hipError_t launch_splitk_reduce(const float* partial, int slices, long long slic
 hipError_t launch_maxpool_fwd(const void* x, void* out, uint8_t* which, int n, int h, int w, int c, hipStream_t s) {
   if (!x || !out || n <= 0 || h <= 0 || w <= 0 || c <= 0) return hipErrorInvalidValue;
   const int oh = (h - 1) / 2 + 1, ow = (w - 1) / 2 + 1;
+  const bool aligned = ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(out)) & 15) == 0 && (reinterpret_cast<uintptr_t>(which) & 7) == 0;
+  if (c % 8 == 0 && aligned) {
+    hipLaunchKernelGGL(maxpool_fwd8_kernel, dim3(blocks_for((long long)n * oh * ow * (c / 8))), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)out, which, n, h, w, c, oh, ow);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for((long long)n * oh * ow * c)), dim3(256), 0, s, (const uint16_t*)x, (uint16_t*)out, which, n, h, w, c, oh, ow);
   return hipGetLastError();
 }
