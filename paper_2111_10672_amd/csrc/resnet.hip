@@ -135,7 +135,7 @@ class ResnetModel : public Model {
   int wgrad_splits(const Conv& c) const {
     const long tiles = (long)((c.cout + 127) / 128) * ((c.k_total() + 127) / 128);
     const long k_tiles = (long)((c.out_rows(batch_) + 63) / 64);
-    long s = (512 + tiles - 1) / tiles;
+    long s = (256 + tiles - 1) / tiles;
     s = std::min(s, std::max(1L, k_tiles / 4));
     return (int)std::max(1L, std::min(s, 1024L));
   }
