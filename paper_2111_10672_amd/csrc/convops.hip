@@ -154,6 +154,27 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const f32x4* __rest
   out[j] = s;
 }
 
+// The same with a bfloat16 result (the input gradient of a product whose k range was cut into slices): eight
+// neighbouring elements per thread, slices added in index order, one rounding at the end.
+__global__ __launch_bounds__(256) void splitk_reduce_bf16_kernel(const f32x4* __restrict__ partial, int slices, long long slice_stride4,
+                                                                 uint4* __restrict__ out, long long numel8) {
+  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (j >= numel8) return;
+  f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
+#pragma unroll 4
+  for (int z = 0; z < slices; ++z) {
+    lo += partial[(size_t)z * slice_stride4 + 2 * j];
+    hi += partial[(size_t)z * slice_stride4 + 2 * j + 1];
+  }
+  auto pack = [](float a, float b) {
+    uint32_t x = __float_as_uint(a), y = __float_as_uint(b);
+    x += 0x7FFFu + ((x >> 16) & 1u);  // round to nearest, ties to even
+    y += 0x7FFFu + ((y >> 16) & 1u);
+    return (x >> 16) | (y & 0xFFFF0000u);
+  };
+  out[j] = make_uint4(pack(lo[0], lo[1]), pack(lo[2], lo[3]), pack(hi[0], hi[1]), pack(hi[2], hi[3]));
+}
+
 // 3x3 window, stride 2, padding 1 (acting as -inf); the first maximum in row-major window order wins.
 // which[n, oh, ow, c] (optional) = index 0..8 of the winning window position.
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ out, uint8_t* __restrict__ which,
@@ -313,6 +334,15 @@ hipError_t launch_splitk_reduce(const float* partial, int slices, long long slic
     return hipGetLastError();
   }
   hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(numel)), dim3(256), 0, s, partial, slices, slice_stride, out, numel, cin, cin_padded);
+  return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce_bf16(const float* partial, int slices, long long slice_stride, void* out, long long numel, hipStream_t s) {
+  if (!partial || !out || slices < 1 || numel <= 0 || numel % 8 || slice_stride % 4 || slice_stride < numel ||
+      (reinterpret_cast<uintptr_t>(partial) & 15) || (reinterpret_cast<uintptr_t>(out) & 15))
+    return hipErrorInvalidValue;
+  hipLaunchKernelGGL(splitk_reduce_bf16_kernel, dim3(blocks_for(numel / 8)), dim3(256), 0, s, reinterpret_cast<const f32x4*>(partial), slices,
+                     slice_stride / 4, reinterpret_cast<uint4*>(out), numel / 8);
   return hipGetLastError();
 }
 

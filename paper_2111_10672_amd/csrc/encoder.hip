@@ -10,6 +10,7 @@
 // MFMA kernel of gemm_dma.hip (attention as batched products over batch x heads); bias, GELU, residual
 // adds and the GELU derivative ride in its epilogue, the residual fan-in of the backward pass rides in the
 // LayerNorm backward kernel.
+#include <algorithm>
 #include <cmath>
 
 #include "model.h"
@@ -214,7 +215,22 @@ class EncoderModel : public Model {
     // ---- head (unit NL + 1) ----
     const bool head_lowest = cut == NL + 1;
     if (int rc = gemm(wgrad(w + p.dlogits, ldv(), w + p.y, H, R, V, H, G(hp(2)), G(hp(3))), s)) return rc;
-    if (int rc = gemm(dgrad(w + p.dlogits, ldv(), R, param_ptrs[hp(2)], V, H, w + p.dy, H), s)) return rc;
+    {
+      // dy = dlogits Wv: a small result over a very long k (the vocabulary).  With too few output tiles to fill
+      // the chip the k range is cut into slices; their float32 partial products go where the logits were (read
+      // for the last time by the loss) and are added up into dy.
+      GemmProblem g = dgrad(w + p.dlogits, ldv(), R, param_ptrs[hp(2)], V, H, w + p.dy, H);
+      const long tiles = (long)((R + 127) / 128) * ((H + 127) / 128);
+      int slices = (int)std::min<long>(256 / std::max<long>(tiles, 1), 16);
+      slices = (int)std::min<long>(slices, std::min<long>(V / 1024, ((long)ldz() * 4) / ((long)H * 4)));
+      if (slices >= 2) {
+        g.k_splits = slices; g.epilogue = Epilogue::StoreF32; g.C = w + p.logits; g.ldc = H;
+        if (int rc = gemm(g, s)) return rc;
+        if (int rc = run("splitk_reduce", (double)(slices * 4 + 2) * R * H, s, [&] {
+              return launch_splitk_reduce_bf16(reinterpret_cast<const float*>(w + p.logits), slices, (long long)R * H, w + p.dy, (long long)R * H, s); }))
+          return rc;
+      } else if (int rc = gemm(g, s)) return rc;
+    }
     void* dout = nullptr;
     if (!head_lowest) {
       dout = w + p.dx[0];

@@ -762,13 +762,15 @@ constexpr size_t small_pair_lds() {
 }
 
 
-// Which products go to the small-product kernel, and with which tile.
+// Which products go to the small-product kernel, and with which tile.  Its workgroups take most of a CU's LDS,
+// so it is for products with at most one tile per CU; with more 64 x 64 tiles than that, two or three
+// workgroups of the ring kernel per CU do better.
 inline long tile_count(const GemmProblem& q, int tm, int tn) { return (long)((q.M + tm - 1) / tm) * ((q.N + tn - 1) / tn) * q.batch * q.k_splits; }
 inline bool small_product_fits(const GemmProblem& q) {
   if (q.a_gather != Gather::None || q.b_gather != Gather::None) return false;
   if (q.N <= 64 && q.M > 64) return tile_count(q, 256, 64) < 256;
   if (q.M <= 64 && q.N > 64) return tile_count(q, 64, 256) < 256;
-  return tile_count(q, 256, 256) < 512 && tile_count(q, 128, 128) < 192;
+  return tile_count(q, 128, 128) < 192 && tile_count(q, 64, 64) <= 256;
 }
 inline bool small_product_tile64(const GemmProblem& q) { return tile_count(q, 64, 64) >= 192; }
 
@@ -820,7 +822,7 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
 }
 
 // Tile choice.  A 256 x 256 tile reads half as many operand bytes per flop from L2 as a 128 x 128 one, which is
-// what large products need; it only pays once there are enough tiles for two rounds over the 256 CUs.  A
+// what large products need.  A
 // dimension of 64 or less (a 64-channel convolution) gets a 64-wide tile so that no matrix-core work is spent
 // on rows that do not exist.  Products with too few tiles for that go to the small-product kernel (plain
 // operands) or to 64 x 64 tiles with a deeper ring (gathered operands): they are bound by latency.
@@ -841,8 +843,16 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
     if (tiles(64, 256) >= 256) return launch_tile<64, 256, 3, 1, 4, LA, LB, GA, GB>(q, stream);
     return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
   }
-  if (tiles(256, 256) >= 512) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
-  if (tiles(128, 128) >= 192) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
+  // 256 x 256 when its tiles make whole rounds over the 256 CUs: one round that covers most of the chip beats
+  // one and a half rounds of 128 x 128 tiles, and so do many rounds; a round and a bit does not.
+  const long t256 = tiles(256, 256);
+  if (q.M >= 256 && q.N >= 256 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
+  // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
+  // alone on its CU needs a third stage in flight instead.
+  if (tiles(128, 128) > 256) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
+  if (tiles(128, 128) >= 192) return launch_tile<128, 128, 3, 2, 2, LA, LB, GA, GB>(q, stream);
+  // 64 x 64: the ring depth that lets every tile be resident at once (two or three workgroups per CU).
+  if (tiles(64, 64) > 512) return launch_tile<64, 64, 3, 2, 2, LA, LB, GA, GB>(q, stream);
   return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
 }
 

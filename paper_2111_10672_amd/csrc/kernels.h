@@ -117,6 +117,8 @@ hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void*
 // (j / cin) * cin_padded + j % cin (drops the zero channels a 3-channel input was padded with).
 hipError_t launch_splitk_reduce(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,
                                 hipStream_t s);
+// out[j] (bfloat16) = sum over slices of partial[slice * slice_stride + j], j < numel; numel a multiple of 8, 16-byte aligned.
+hipError_t launch_splitk_reduce_bf16(const float* partial, int slices, long long slice_stride, void* out, long long numel, hipStream_t s);
 // 3x3 / stride 2 / padding 1 max-pool of x [n, h, w, c]; which (optional, [n, oh, ow, c]) records the winning window position.
 hipError_t launch_maxpool_fwd(const void* x, void* out, uint8_t* which, int n, int h, int w, int c, hipStream_t s);
 hipError_t launch_maxpool_bwd(const void* dout, const uint8_t* which, void* da, int n, int h, int w, int c, hipStream_t s);

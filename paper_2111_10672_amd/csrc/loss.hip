@@ -70,6 +70,80 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
   if (first == 0) row_loss[row] = lse - ((unsigned)y < (unsigned)classes ? z[y] : 0.f);
 }
 
+// Long rows (a vocabulary of tens of thousands): one workgroup of 512 threads per row holds the whole row in
+// registers as 16-byte vectors, so the logits are read from memory exactly once, with every load of the row in
+// flight together; the exponentials are kept and only scaled for the gradient.  Columns between `classes` and
+// the pitch count as minus infinity on the way in and come out as zero.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kXentThreads = 512, kXentVecs = 16;   // rows of up to 512 * 16 * 4 = 32768 columns, pitch included
+__device__ __forceinline__ void store_dz4(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
+__device__ __forceinline__ void store_dz4(uint16_t* p, const f32x4& v) {
+  uint32_t u[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { u[e] = __float_as_uint(v[e]); u[e] += 0x7FFFu + ((u[e] >> 16) & 1u); }
+  *reinterpret_cast<uint2*>(p) = make_uint2((u[0] >> 16) | (u[1] & 0xFFFF0000u), (u[2] >> 16) | (u[3] & 0xFFFF0000u));
+}
+template <typename DZ>
+__global__ __launch_bounds__(kXentThreads) void softmax_xent_long_kernel(const float* __restrict__ logits, int ldz,
+                                                                        const int32_t* __restrict__ labels, int rows, int classes,
+                                                                        DZ* __restrict__ dz, int lddz, float* __restrict__ row_loss) {
+  __shared__ float red[kXentThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x;
+  const float* z = logits + (size_t)row * ldz;
+  f32x4 v[kXentVecs];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kXentVecs; ++i) {
+    const int c = 4 * ((int)threadIdx.x + kXentThreads * i);
+    v[i] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (c + 4 <= ldz) v[i] = *reinterpret_cast<const f32x4*>(z + c);
+  }
+#pragma unroll
+  for (int i = 0; i < kXentVecs; ++i) {
+    const int c = 4 * ((int)threadIdx.x + kXentThreads * i);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (c + e >= classes) v[i][e] = -INFINITY;
+      m = fmaxf(m, v[i][e]);
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  m = red[0];
+#pragma unroll
+  for (int w = 1; w < kXentThreads / 64; ++w) m = fmaxf(m, red[w]);
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kXentVecs; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[i][e] = expf(v[i][e] - m); s += v[i][e]; }
+  s = wave_sum(s);
+  if (lane == 0) red[wave] = s;
+  __syncthreads();
+  s = red[0];
+#pragma unroll
+  for (int w = 1; w < kXentThreads / 64; ++w) s += red[w];
+  const int y = labels[row];
+  const float scale = 1.f / (s * (float)rows), inv_rows = 1.f / (float)rows;
+  DZ* out = dz + (size_t)row * lddz;
+#pragma unroll
+  for (int i = 0; i < kXentVecs; ++i) {
+    const int c = 4 * ((int)threadIdx.x + kXentThreads * i);
+    if (c + 4 <= lddz) {
+      f32x4 g = v[i] * scale;
+      // a label outside [0, classes) contributes no target term
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (c + e == y && y < classes) g[e] -= inv_rows;
+      store_dz4(out + c, g);
+    }
+  }
+  if (threadIdx.x == 0) row_loss[row] = m + logf(s) - ((unsigned)y < (unsigned)classes ? z[y] : 0.f);
+}
+
 // Adds the per-row losses in a fixed order (same result on every run) and stores the mean.
 __global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ row_loss, int rows, float* __restrict__ out) {
   __shared__ float red[4];
@@ -139,6 +213,17 @@ hipError_t launch_softmax_xent(const float* logits, int ldz, const int32_t* labe
       hipLaunchKernelGGL((softmax_xent_one_block_kernel<float>), dim3(1), dim3(256), 0, stream, logits, ldz, labels, rows, classes, lpr, (float*)dz, lddz, row_loss, loss_out);
     else
       hipLaunchKernelGGL((softmax_xent_one_block_kernel<uint16_t>), dim3(1), dim3(256), 0, stream, logits, ldz, labels, rows, classes, lpr, (uint16_t*)dz, lddz, row_loss, loss_out);
+    return hipGetLastError();
+  }
+  const bool vec_ok = ldz % 4 == 0 && lddz % 4 == 0 && (reinterpret_cast<uintptr_t>(logits) & 15u) == 0 && (reinterpret_cast<uintptr_t>(dz) & 15u) == 0;
+  if (classes > 2048 && vec_ok && (ldz > lddz ? ldz : lddz) <= kXentThreads * kXentVecs * 4) {
+    if (dz_dtype == DType::F32)
+      hipLaunchKernelGGL((softmax_xent_long_kernel<float>), dim3(rows), dim3(kXentThreads), 0, stream, logits, ldz, labels, rows, classes, (float*)dz, lddz, row_loss);
+    else
+      hipLaunchKernelGGL((softmax_xent_long_kernel<uint16_t>), dim3(rows), dim3(kXentThreads), 0, stream, logits, ldz, labels, rows, classes, (uint16_t*)dz, lddz, row_loss);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(256), 0, stream, row_loss, rows, loss_out);
     return hipGetLastError();
   }
   const bool wide = classes > 2048;

@@ -9,6 +9,7 @@ namespace spb {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxChunks = 4;  // 16-byte chunks per lane: rows of up to 64 * 4 * 8 = 2048 elements
 constexpr float kLnEps = 1e-5f;
@@ -165,6 +166,103 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const uint16_t* __re
     partial[(size_t)blockIdx.x * 2 * width + col] = ((sh[col] + sh[2 * width + col]) + sh[4 * width + col]) + sh[6 * width + col];
 }
 
+// The same backward pass for the widths that split evenly over lanes: a row is held by LPR lanes with CPL
+// 16-byte chunks each (width = LPR * CPL * 8), a wavefront works on 64 / LPR rows at a time and takes ITERS such
+// groups.  Everything the wavefront will read (scale, statistics, all its rows) is requested before the first
+// value is used, so the kernel pays one memory latency, not one per row.  Workgroup b handles rows
+// b * kRows .. b * kRows + kRows - 1 and writes one partial column sum (the same layout as above).
+template <int LPR, int CPL, int ITERS>
+__global__ __launch_bounds__(256) void layernorm_bwd_even_kernel(const uint16_t* __restrict__ dy, int lddy, const uint16_t* __restrict__ x,
+                                                                 int ldx, const int32_t* __restrict__ rows, const float* __restrict__ stats,
+                                                                 const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ res, int ldres,
+                                                                 uint16_t* __restrict__ dx, int lddx, float* __restrict__ partial, int n_rows) {
+  constexpr int RPW = 64 / LPR, kRows = 4 * RPW * ITERS, kWidth = LPR * CPL * 8;
+  extern __shared__ float sh[];  // [4 * RPW row groups][2][kWidth]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPR, l = lane % LPR;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  u32x4 graw[CPL], dyraw[ITERS][CPL], xraw[ITERS][CPL], rraw[ITERS][CPL];
+  float mean[ITERS], rstd[ITERS];
+  size_t xrow[ITERS];
+  bool live[ITERS];
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) graw[i] = *reinterpret_cast<const u32x4*>(gamma + (l + LPR * i) * 8);
+#pragma unroll
+  for (int j = 0; j < ITERS; ++j) {
+    const int r = blockIdx.x * kRows + (j * 4 + wave) * RPW + sub;
+    live[j] = r < n_rows;
+    const int rc = live[j] ? r : n_rows - 1;
+    xrow[j] = rows ? rows[rc] : rc;
+    mean[j] = stats[2 * rc];
+    rstd[j] = stats[2 * rc + 1];
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      const int c = (l + LPR * i) * 8;
+      dyraw[j][i] = live[j] ? *reinterpret_cast<const u32x4*>(dy + (size_t)rc * lddy + c) : zero;
+      xraw[j][i] = *reinterpret_cast<const u32x4*>(x + xrow[j] * ldx + c);
+      rraw[j][i] = res && live[j] ? *reinterpret_cast<const u32x4*>(res + (size_t)rc * ldres + c) : zero;
+    }
+  }
+  float dgam[CPL][8], dbet[CPL][8];
+#pragma unroll
+  for (int i = 0; i < CPL; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dgam[i][e] = 0.f; dbet[i][e] = 0.f; }
+#pragma unroll
+  for (int j = 0; j < ITERS; ++j) {
+    float g[CPL][8], xh[CPL][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      float d[8], xv[8], gm[8];
+      unpack8(dyraw[j][i], d);
+      unpack8(xraw[j][i], xv);
+      unpack8(graw[i], gm);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        xh[i][e] = (xv[e] - mean[j]) * rstd[j];
+        g[i][e] = d[e] * gm[e];
+        s1 += g[i][e];
+        s2 += g[i][e] * xh[i][e];
+        dgam[i][e] += d[e] * xh[i][e];   // a row past the end has d = 0
+        dbet[i][e] += d[e];
+      }
+    }
+    if (dx) {
+#pragma unroll
+      for (int o = LPR / 2; o > 0; o >>= 1) { s1 += __shfl_xor(s1, o, 64); s2 += __shfl_xor(s2, o, 64); }
+      const float m1 = s1 / (float)kWidth, m2 = s2 / (float)kWidth;
+      if (live[j]) {
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+          float o[8], rv[8];
+          unpack8(rraw[j][i], rv);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (g[i][e] - m1 - xh[i][e] * m2) * rstd[j] + rv[e];
+          *reinterpret_cast<u32x4*>(dx + xrow[j] * lddx + (l + LPR * i) * 8) = pack8(o);
+        }
+      }
+    }
+  }
+  // add the 4 * RPW row groups' column sums in group order
+  float* mine = sh + (size_t)(wave * RPW + sub) * 2 * kWidth;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    const int c = (l + LPR * i) * 8;
+    *reinterpret_cast<f32x4*>(mine + c) = f32x4{dgam[i][0], dgam[i][1], dgam[i][2], dgam[i][3]};
+    *reinterpret_cast<f32x4*>(mine + c + 4) = f32x4{dgam[i][4], dgam[i][5], dgam[i][6], dgam[i][7]};
+    *reinterpret_cast<f32x4*>(mine + kWidth + c) = f32x4{dbet[i][0], dbet[i][1], dbet[i][2], dbet[i][3]};
+    *reinterpret_cast<f32x4*>(mine + kWidth + c + 4) = f32x4{dbet[i][4], dbet[i][5], dbet[i][6], dbet[i][7]};
+  }
+  __syncthreads();
+  for (int col = threadIdx.x; col < 2 * kWidth; col += 256) {
+    float t = sh[col];
+#pragma unroll
+    for (int q = 1; q < 4 * RPW; ++q) t += sh[(size_t)q * 2 * kWidth + col];
+    partial[(size_t)blockIdx.x * 2 * kWidth + col] = t;
+  }
+}
+
 // out_a[c] = sum_b partial[b][0][c];  out_b[c] = sum_b partial[b][1][c].  A workgroup takes 16 columns: thread
 // (g, c) adds blocks g, g + 16, ... of column c in order (16 neighbouring threads read 64 contiguous bytes), then
 // the 16 group sums of a column are added in group order: the same bits on every run.
@@ -174,8 +272,10 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   const int c = threadIdx.x & 15, g = threadIdx.x >> 4;
   const int col = blockIdx.x * 16 + c;
   float s = 0.f;
-  if (col < 2 * width)
+  if (col < 2 * width) {
+#pragma unroll 8
     for (int b = g; b < n_blocks; b += 16) s += partial[(size_t)b * 2 * width + col];
+  }
   sh[g][c] = s;
   __syncthreads();
   if (threadIdx.x < 16 && col < 2 * width) {
@@ -347,10 +447,27 @@ hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx
   if (!dy || !x || !stats || !gamma || !partial || !dgamma || !dbeta || n_rows <= 0) return hipErrorInvalidValue;
   if (!row_ok(width, lddy) || !row_ok(width, ldx) || (dx && !row_ok(width, lddx)) || (res && !row_ok(width, ldres))) return hipErrorInvalidValue;
   if (!a16(dy) || !a16(x) || !a16(gamma) || !a16(dx) || !a16(res)) return hipErrorInvalidValue;
-  const int blocks = (n_rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
-  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(blocks), dim3(256), (size_t)8 * width * sizeof(float), s, (const uint16_t*)dy, lddy,
-                     (const uint16_t*)x, ldx, rows, stats, (const uint16_t*)gamma, (const uint16_t*)res, ldres, (uint16_t*)dx, lddx,
-                     partial, n_rows, width);
+  int blocks = 0;
+  auto even = [&](auto kernel, int lpr, int iters) {
+    const int rows_per_block = 4 * (64 / lpr) * iters;
+    blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), (size_t)4 * (64 / lpr) * 2 * width * sizeof(float), s, (const uint16_t*)dy, lddy,
+                       (const uint16_t*)x, ldx, rows, stats, (const uint16_t*)gamma, (const uint16_t*)res, ldres, (uint16_t*)dx, lddx,
+                       partial, n_rows);
+  };
+  // every variant gives a workgroup at least kLnRowsPerBlock rows, so the partial sums fit the buffer sized above
+  const int chunks = width / 8;
+  if (chunks == 96) even(layernorm_bwd_even_kernel<32, 3, 2>, 32, 2);
+  else if (chunks == 64) even(layernorm_bwd_even_kernel<64, 1, 4>, 64, 4);
+  else if (chunks == 128) even(layernorm_bwd_even_kernel<64, 2, 4>, 64, 4);
+  else if (chunks == 16) even(layernorm_bwd_even_kernel<16, 1, 1>, 16, 1);
+  else if (chunks == 8) even(layernorm_bwd_even_kernel<8, 1, 1>, 8, 1);
+  else {
+    blocks = (n_rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock;
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(blocks), dim3(256), (size_t)8 * width * sizeof(float), s, (const uint16_t*)dy, lddy,
+                       (const uint16_t*)x, ldx, rows, stats, (const uint16_t*)gamma, (const uint16_t*)res, ldres, (uint16_t*)dx, lddx,
+                       partial, n_rows, width);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 15) / 16), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
