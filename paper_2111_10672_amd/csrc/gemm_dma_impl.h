@@ -100,7 +100,7 @@ struct TileSource {
         constexpr int kRowChunks = ROWS / 8;
         k = slot / kRowChunks;
         const int pc = slot % kRowChunks;
-        gr = row0 + (((pc - krow_rot<ROWS>(k)) & (kRowChunks - 1)) << 3);
+        gr = row0 + (((pc - krow_rot<ROWS>(k) + kRowChunks) % kRowChunks) << 3);
       }
       k_in_tile[i] = k;
       in_rows[i] = gr < nrows;
@@ -206,7 +206,7 @@ __device__ __forceinline__ u32x4 read_fragment(const char* tile, int frag_row0, 
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int k = 16 * kg + 8 * (g >> 1) + 4 * h + (j >> 2);
-      const int pc = ((row >> 3) + krow_rot<ROWS>(k)) & (kRowChunks - 1);
+      const int pc = ((row >> 3) + krow_rot<ROWS>(k)) % kRowChunks;
       const char* addr = tile + k * (ROWS * 2) + pc * 16 + (row & 7) * 2;
       // Written as assembly: through the builtin the compiler cannot tell this read from the in-flight
       // direct-to-LDS tiles and drains them all (vmcnt 0) first.
@@ -330,9 +330,10 @@ template <int WN, int PARTS = 1>
 __device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float* stage, int piece_row, int col_base, int lane, long long c_offset,
                                                int rows = 32, int part_stride = 0) {
   constexpr int kPitch = WN + 4;
-  constexpr int kPerRow = WN / 4;             // 4-column units per row; 64 % kPerRow == 0, so a lane's column never changes
+  constexpr int kPerRow = WN / 4;             // 4-column units per row; a lane's column never changes
+  constexpr int kRowStep = 64 / kPerRow;      // rows per pass; with 96 columns the last lanes of the wave sit out
   const int c = (lane % kPerRow) * 4, n = col_base + c;
-  if (n >= p.N) return;
+  if (n >= p.N || lane >= kPerRow * kRowStep) return;
   const bool whole = n + 4 <= p.N;
   f32x4 b = {0.f, 0.f, 0.f, 0.f};
   if (p.bias && whole) {
@@ -341,7 +342,7 @@ __device__ __forceinline__ void store_rows_f32(const GemmParams& p, const float*
     b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xFFFF0000u);
   }
 #pragma unroll 1
-  for (int row = lane / kPerRow; row < rows; row += 64 / kPerRow) {
+  for (int row = lane / kPerRow; row < rows; row += kRowStep) {
     const int m = piece_row + row;
     if (m >= p.M) break;
     f32x4 v = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c);
@@ -362,9 +363,9 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
                                                 const u32x4* xpre = nullptr) {
   constexpr int kPitch = WN + 4;
   constexpr int kPerRow = WN / 8;             // 8-column units per row; a lane's column never changes
-  constexpr int kRowStep = 64 / kPerRow;
+  constexpr int kRowStep = 64 / kPerRow;      // rows per pass; with 96 columns the last lanes of the wave sit out
   const int c = (lane % kPerRow) * 8, n = col_base + c;
-  if (n >= p.N) return;
+  if (n >= p.N || lane >= kPerRow * kRowStep) return;
   const int mode = p.epilogue;
   const bool plain = mode == (int)Epilogue::BiasAct;
   bf16_t* aux = plain ? static_cast<bf16_t*>(p.aux_out) : nullptr;
@@ -568,7 +569,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 #pragma unroll
         for (int j = 0; j < kTileK / kPhases; ++j) {
           const int k = sum_phase + j * kPhases;
-          const int pc = (sum_chunk + krow_rot<BM>(k)) & (kChunks - 1);
+          const int pc = (sum_chunk + krow_rot<BM>(k)) % kChunks;
           float f[8];
           unpack_bf16x8(*reinterpret_cast<const u32x4*>(as + k * (BM * 2) + pc * 16), f);
 #pragma unroll
@@ -772,7 +773,8 @@ inline bool small_product_fits(const GemmProblem& q) {
   if (q.M <= 64 && q.N > 64) return tile_count(q, 64, 256) < 256;
   return tile_count(q, 128, 128) < 192 && tile_count(q, 64, 64) <= 256;
 }
-inline bool small_product_tile64(const GemmProblem& q) { return tile_count(q, 64, 64) >= 192; }
+// 32 x 32 tiles only while they still make a single round over the CUs.
+inline bool small_product_tile64(const GemmProblem& q) { return tile_count(q, 64, 64) >= 192 || tile_count(q, 32, 32) > 256; }
 
 template <int BM, int BN, Layout LA, Layout LB>
 hipError_t launch_small(const GemmProblem& q, hipStream_t stream) {
@@ -845,6 +847,11 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   }
   // 256 x 256 when its tiles make whole rounds over the 256 CUs: one round that covers most of the chip beats
   // one and a half rounds of 128 x 128 tiles, and so do many rounds; a round and a bit does not.
+  // A 256 x 192 tile when that makes ONE round with (nearly) every CU busy: 3072 or 2304 columns against 4096
+  // rows give 256 or 192 such tiles where 256 x 256 gives 192 or 144.
+  const long t192 = tiles(256, 192);
+  if (q.M >= 256 && t192 >= 176 && t192 <= 256 && (long)((q.N + 191) / 192) * 192 * 20 <= (long)q.N * 21)
+    return launch_tile<256, 192, 2, 4, 2, LA, LB, GA, GB>(q, stream);
   const long t256 = tiles(256, 256);
   if (q.M >= 256 && q.N >= 256 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
   // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
