@@ -32,6 +32,10 @@ def parse():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
+    ap.add_argument("--launch", choices=["auto", "graph", "eager"], default="auto",
+                    help="how the timed steps are launched: replayed HIP graphs (launch-bound workloads: the perceptrons), "
+                         "eagerly on one stream (the library then runs weight gradients on a second stream of its own, "
+                         "which a graph replay does not profit from), or auto = graph for perceptrons, eager otherwise")
     ap.add_argument("--eager", action="store_true",
                     help="launch the timed steps eagerly instead of replaying HIP graphs (for counter collection, "
                          "which does not survive graph replay on this ROCm)")
@@ -280,7 +284,8 @@ def main():
     # One HIP graph per depth: the kernels of spb_forward(k) + spb_backward_truncated(k), nothing else.
     # (graph capture needs a stream of its own; eager launches stay on the default stream, the only one the
     # counter-collection mode of the profiler copes with)
-    stream = torch.cuda.current_stream() if args.eager else torch.cuda.Stream()
+    eager = args.eager or args.launch == "eager" or (args.launch == "auto" and cfg["family"] != "mlp")
+    stream = torch.cuda.current_stream() if eager else torch.cuda.Stream()
     graphs = {}
     with torch.cuda.stream(stream):
         for k in depths:
@@ -294,7 +299,7 @@ def main():
                 model.step(dev, self.k)
 
         for k in depths:
-            if args.eager:
+            if eager:
                 graphs[k] = Eager(k)
                 continue
             g = torch.cuda.CUDAGraph()
@@ -383,7 +388,7 @@ def main():
         "dtype": "f32" if is_f32 else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: {cfg['family']} {cfg['dims'] if 'dims' in cfg else ''} batch {cfg['batch']}, "
                                f"depth sweep k={depths}, steps shared evenly between depths",
-                   "launch": "eager" if args.eager else "hip_graph_replay", "steps_per_depth": per_depth},
+                   "launch": "eager" if eager else "hip_graph_replay", "steps_per_depth": per_depth},
         "samples_per_s_by_depth": {str(k): round(cfg["batch"] / (ms * 1e-3), 1) for k, ms in zip(depths, depth_ms)},
         "ms_by_depth": {str(k): round(ms, 6) for k, ms in zip(depths, depth_ms)},
         "workspace_bytes_by_depth": {str(k): spb.spb_workspace_size(model.handle, k) for k in depths},

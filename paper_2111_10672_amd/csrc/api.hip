@@ -1,4 +1,5 @@
 // The C ABI (include/spb.h): argument checks on the host, then the family's step driver.
+#include <cstdlib>
 #include "model.h"
 
 #include <cstring>
@@ -31,6 +32,63 @@ int Model::replay(const char* name, int count, hipStream_t s) {
   for (int i = 0; i < count; ++i)
     if (int rc = check(pr.pair ? launch_gemm_pair(pr.first, pr.second, s) : launch_gemm(pr.first, s), name)) return rc;
   return SPB_OK;
+}
+
+Model::~Model() {
+  if (side_) (void)hipStreamDestroy(side_);
+  if (fork_ev_) (void)hipEventDestroy(fork_ev_);
+  if (join_ev_) (void)hipEventDestroy(join_ev_);
+  for (auto e : mark_ev_) if (e) (void)hipEventDestroy(e);
+}
+
+void Model::ensure_side_stream(hipStream_t s) {
+  if (side_) return;
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
+  hipStream_t q = nullptr;
+  hipEvent_t ev[2 + kMarks] = {};
+  bool ok = hipStreamCreateWithFlags(&q, hipStreamNonBlocking) == hipSuccess;
+  for (int i = 0; ok && i < 2 + kMarks; ++i) ok = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) == hipSuccess;
+  if (ok) {
+    side_ = q; fork_ev_ = ev[0]; join_ev_ = ev[1];
+    for (int i = 0; i < kMarks; ++i) mark_ev_[i] = ev[2 + i];
+    return;
+  }
+  (void)hipGetLastError();
+  if (q) (void)hipStreamDestroy(q);
+  for (auto e : ev) if (e) (void)hipEventDestroy(e);
+}
+
+int Model::mark() {
+  if (!forked_) return -1;
+  const int m = next_mark_;
+  if (hipEventRecord(mark_ev_[m], side_) != hipSuccess) { (void)hipGetLastError(); return -2; }  // -2: wait for everything instead
+  next_mark_ = (next_mark_ + 1) % kMarks;
+  return m;
+}
+
+int Model::wait_mark(hipStream_t s, int m) {
+  if (m == -2) return join(s);
+  if (m < 0 || !side_) return SPB_OK;
+  return check(hipStreamWaitEvent(s, mark_ev_[m], 0), "wait_mark");
+}
+
+hipStream_t Model::fork(hipStream_t s) {
+  if (!side_ || timer.enabled()) return s;
+  // A graph replays its parallel branches no faster than a single chain here, and every fork and join adds an
+  // edge to it: while s is being captured everything stays on s.
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess || st != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return s; }
+  if (hipEventRecord(fork_ev_, s) != hipSuccess || hipStreamWaitEvent(side_, fork_ev_, 0) != hipSuccess) { (void)hipGetLastError(); return s; }
+  forked_ = true;
+  return side_;
+}
+
+int Model::join(hipStream_t s) {
+  if (!forked_) return SPB_OK;
+  forked_ = false;
+  if (int rc = check(hipEventRecord(join_ev_, side_), "join")) return rc;
+  return check(hipStreamWaitEvent(s, join_ev_, 0), "join");
 }
 
 int Model::gemm(const GemmProblem& p, hipStream_t s) {
@@ -226,6 +284,7 @@ int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_
   const size_t need = m->impl->workspace_size(k);
   SPB_REQUIRE(workspace && workspace_bytes >= need, SPB_ERR_WORKSPACE, "spb_forward: workspace of %zu bytes, depth %d needs %zu", workspace_bytes, k, need);
   SPB_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, SPB_ERR_WORKSPACE, "spb_forward: workspace is not 256-byte aligned");
+  m->impl->ensure_side_stream(static_cast<hipStream_t>(stream));
   int rc = m->impl->forward(x, labels, loss_rows, k, workspace, loss_out, static_cast<hipStream_t>(stream));
   if (rc != SPB_OK) return rc;
   m->impl->stashed_k = k;
@@ -251,7 +310,9 @@ int spb_backward_truncated(spb_model* m, int32_t k, void* stream) {
   SPB_REQUIRE(k <= m->impl->stashed_k, SPB_ERR_STATE, "spb_backward_truncated: depth %d, but the forward pass stashed for depth %d", k, m->impl->stashed_k);
   if (k == 0) return SPB_OK;
   if (int rc = grads_ok(m, k, "spb_backward_truncated")) return rc;
-  return m->impl->backward(k, static_cast<hipStream_t>(stream));
+  const int rc = m->impl->backward(k, static_cast<hipStream_t>(stream));
+  const int rj = m->impl->finish(static_cast<hipStream_t>(stream));  // the caller's stream waits for the side stream's kernels
+  return rc != SPB_OK ? rc : rj;
 }
 
 int spb_grad_buffers(const spb_model* m, int32_t k, spb_grad_view* out, int32_t cap, int32_t* n_out) {

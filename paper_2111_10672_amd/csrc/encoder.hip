@@ -214,7 +214,8 @@ class EncoderModel : public Model {
 
     // ---- head (unit NL + 1) ----
     const bool head_lowest = cut == NL + 1;
-    if (int rc = gemm(wgrad(w + p.dlogits, ldv(), w + p.y, H, R, V, H, G(hp(2)), G(hp(3))), s)) return rc;
+    // Weight gradients go to the side stream (they feed nothing in this pass); the input-gradient chain stays on s.
+    if (int rc = gemm(wgrad(w + p.dlogits, ldv(), w + p.y, H, R, V, H, G(hp(2)), G(hp(3))), fork(s))) return rc;
     {
       // dy = dlogits Wv: a small result over a very long k (the vocabulary).  With too few output tiles to fill
       // the chip the k range is cut into slices; their float32 partial products go where the logits were (read
@@ -248,20 +249,22 @@ class EncoderModel : public Model {
       const void* xin = w + p.xout[i];
       auto P = [&](int j) { return param_ptrs[lp(i, j)]; };
       auto GP = [&](int j) { return G(lp(i, j)); };
+      // The previous layer's weight gradients read dF, dh and dqkv, which this layer is about to overwrite.
+      if (int rc = join(s)) return rc;
       // feed-forward half
-      if (int rc = gemm(wgrad(dout, H, w + b.f, F, M, H, F, GP(W2W), GP(W2B)), s)) return rc;
+      if (int rc = gemm(wgrad(dout, H, w + b.f, F, M, H, F, GP(W2W), GP(W2B)), fork(s))) return rc;
       {
         GemmProblem g = dgrad(dout, H, M, P(W2W), H, F, w + p.dF, F);   // dz1 = (dout W2) * gelu'(z1)
         g.epilogue = Epilogue::GeluBwdStore; g.mask = w + b.z1; g.ldmask = F;
         if (int rc = gemm(g, s)) return rc;
       }
-      if (int rc = gemm(wgrad(w + p.dF, F, w + b.v, H, M, F, H, GP(W1W), GP(W1B)), s)) return rc;
+      if (int rc = gemm(wgrad(w + p.dF, F, w + b.v, H, M, F, H, GP(W1W), GP(W1B)), fork(s))) return rc;
       if (int rc = gemm(dgrad(w + p.dF, F, M, P(W1W), F, H, w + p.dv, H), s)) return rc;
       if (int rc = run("layernorm_bwd", 4 * mh, s, [&] {   // dh = dout + LN2 backward
             return launch_layernorm_bwd(w + p.dv, H, w + b.h, H, nullptr, reinterpret_cast<const float*>(w + b.stats2), P(LN2W), dout, H,
                                         w + p.dh, H, partial, GP(LN2W), GP(LN2B), M, H, s); })) return rc;
       // attention half
-      if (int rc = gemm(wgrad(w + p.dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), s)) return rc;
+      if (int rc = gemm(wgrad(w + p.dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), fork(s))) return rc;
       if (int rc = gemm(dgrad(w + p.dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
       const char* qbase = w + b.qkv;
       if (attention_fused_accepts(S, D, 3 * H, H)) {
@@ -294,7 +297,7 @@ class EncoderModel : public Model {
       if (int rc = attn_out("attn_bwd_dq", Layout::RowK, w + p.dscore, S, per_matrix(), bf(qbase, (size_t)H), 0)) return rc;
       if (int rc = attn_out("attn_bwd_dk", Layout::KRow, w + p.dscore, S, per_matrix(), qbase, 1)) return rc;
       }
-      if (int rc = gemm(wgrad(w + p.dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), s)) return rc;
+      if (int rc = gemm(wgrad(w + p.dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), fork(s))) return rc;
       if (int rc = gemm(dgrad(w + p.dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
       void* dx = lowest ? nullptr : w + p.dx[which ^ 1];
       if (int rc = run("layernorm_bwd", (lowest ? 2 : 4) * mh, s, [&] {   // dx = dh + LN1 backward; the lowest unit forms no input gradient

@@ -48,7 +48,7 @@ class KernelTimer {
 
 class Model {
  public:
-  virtual ~Model() = default;
+  virtual ~Model();
   virtual size_t workspace_size(int k) const = 0;
   virtual int forward(const void* x, const int32_t* labels, const int32_t* loss_rows, int k, void* ws, float* loss_out, hipStream_t s) = 0;
   virtual int backward(int k, hipStream_t s) = 0;
@@ -66,11 +66,34 @@ class Model {
   std::map<std::string, Product> last_product;  // per kernel class, the most recent product or pair (kept while timing is on)
   int replay(const char* name, int count, hipStream_t s);
 
+  // Creates the side stream (see fork) unless s is being captured into a graph right now; called by the C ABI
+  // before a forward pass, so a model built on a machine without a GPU never touches the runtime.
+  void ensure_side_stream(hipStream_t s);
+  int finish(hipStream_t s) { return join(s); }   // after a backward pass: s waits for whatever is still on the side stream
+
  protected:
+  // Work that does not feed the main chain of a backward pass (a layer's weight gradient, beside its input
+  // gradient) goes to a second stream so that both kinds of kernel share the chip: fork(s) makes the side
+  // stream wait for everything enqueued on s so far and returns it; join(s) makes s wait for everything enqueued
+  // on the side stream.  While kernels are being timed, while s is being captured into a graph, or before the
+  // side stream exists, fork returns s itself and everything stays in one order.
+  hipStream_t fork(hipStream_t s);
+  int join(hipStream_t s);
+  // Finer than join: mark() stands for everything enqueued on the side stream so far (-1 when nothing is forked),
+  // wait_mark(s, m) makes s wait for just that.  At most kMarks marks are live at a time.
+  static constexpr int kMarks = 8;
+  int mark();
+  int wait_mark(hipStream_t s, int m);
   int gemm(const GemmProblem& p, hipStream_t s);
   int gemm_pair(const GemmProblem& d, const GemmProblem& w, hipStream_t s);  // see launch_gemm_pair
   int run(const char* name, double bytes, hipStream_t s, const std::function<hipError_t()>& launch);
   int check(hipError_t e, const char* what);
+
+ private:
+  hipStream_t side_ = nullptr;
+  hipEvent_t fork_ev_ = nullptr, join_ev_ = nullptr, mark_ev_[8] = {};
+  int next_mark_ = 0;
+  bool forked_ = false;
 };
 
 std::unique_ptr<Model> make_mlp(const spb_model_desc& d);

@@ -373,22 +373,32 @@ class ResnetModel : public Model {
       void* dy = w + p.g[3];
       void* da = w + p.g[4];
       const int last = (int)b.convs.size() - 1;
+      // Weight gradients run on the side stream, beside the chain of input gradients.  They read the gradient
+      // buffers dy alternates between (slots 3 and 5) and slot 6; the block above may still be reading them.
+      if (int rc = join(s)) return rc;
+      int reader[2] = {-1, -1};   // mark of the weight-gradient product that last read slot 3 / slot 5
+      int dy_slot = 0;            // dy lives in slot 3 + 2 * dy_slot
       // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut
       if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart, s)) return rc;
       for (int j = last; j >= 1; --j) {
         const void* in_j = w + u.conv[j - 1].a;
-        if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[j].w]), s)) return rc;
+        if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[j].w]), fork(s))) return rc;
+        reader[dy_slot] = mark();
         if (int rc = conv_dgrad(b.convs[j], dy, param_ptrs[b.convs[j].w], nullptr, da, s)) return rc;
-        void* dy_next = w + p.g[j % 2 ? 5 : 3];
+        const int next_slot = dy_slot ^ 1;
+        void* dy_next = w + p.g[3 + 2 * next_slot];
+        if (int rc = wait_mark(s, reader[next_slot])) return rc;   // whoever read that slot is done with it
+        reader[next_slot] = -1;
         if (int rc = affine_bwd(b.convs[j - 1], da, in_j, w + u.conv[j - 1].y, dy_next, nullptr, apart, s)) return rc;
         dy = dy_next;
+        dy_slot = next_slot;
       }
-      if (int rc = conv_wgrad(b.convs[0], x_in, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[0].w]), s)) return rc;
+      if (int rc = conv_wgrad(b.convs[0], x_in, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[0].w]), fork(s))) return rc;
       const void* shortcut_grad = dsum;
       if (b.has_proj) {
         void* dys = w + p.g[6];
         if (int rc = affine_bwd(b.proj, dsum, nullptr, w + u.proj.y, dys, nullptr, apart, s)) return rc;
-        if (int rc = conv_wgrad(b.proj, x_in, dys, wpart, static_cast<float*>(grad_ptrs[b.proj.w]), s)) return rc;
+        if (int rc = conv_wgrad(b.proj, x_in, dys, wpart, static_cast<float*>(grad_ptrs[b.proj.w]), fork(s))) return rc;
         if (need_dx) {
           if (int rc = conv_dgrad(b.proj, dys, param_ptrs[b.proj.w], nullptr, w + p.g[7], s)) return rc;
           shortcut_grad = w + p.g[7];
@@ -402,6 +412,7 @@ class ResnetModel : public Model {
     }
     // ---- stem (unit 0), reached only at full depth ----
     if (cut == 0) {
+      if (int rc = join(s)) return rc;   // slot 3 is written next
       const UnitBuf& su = p.unit[0];
       const void* d = dout;
       if (pool_) {
