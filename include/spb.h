@@ -25,6 +25,14 @@
  *   - Work is enqueued on the caller's stream (a hipStream_t passed as void*);
  *     calls return without waiting for the device and may be captured into a
  *     HIP graph.  Calls on one model must not overlap in time.
+ *   - A model owns one more HIP stream and a few events (no device memory),
+ *     created by its first spb_forward outside a graph capture and released by
+ *     spb_model_destroy.  spb_backward_truncated runs weight-gradient kernels on
+ *     it beside the input-gradient chain; it first makes that stream wait for the
+ *     caller's and, before it returns, makes the caller's stream wait for it, so
+ *     to the caller everything is ordered on the stream that was passed.  While
+ *     that stream is being captured, and while kernel timing is on, the extra
+ *     stream is not used.  Results are the same bits in every case.
  *   - All matrices are row-major.  Activations of perceptrons are
  *     [batch, features].
  *   - A model needs a GPU; there is no host fallback.
