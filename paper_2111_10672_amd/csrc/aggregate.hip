@@ -33,11 +33,7 @@ struct AggTable {
 };
 
 __device__ __forceinline__ float bf(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-__device__ __forceinline__ uint16_t to_bf16(float v) {
-  uint32_t u = __float_as_uint(v);
-  u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest, ties to even
-  return (uint16_t)(u >> 16);
-}
+__device__ __forceinline__ uint16_t to_bf16(float v) { return bf16_round(v); }
 
 __global__ __launch_bounds__(256) void aggregate_update_kernel(AggTable tab) {
   // which tensor: the last one whose first_block is not past this workgroup (uniform, a handful of compares)

@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
     for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
     float sum = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { s[j][r] = expf(s[j][r] - m); sum += s[j][r]; }
+    for (int j = 0; j < 4; ++j) { s[j][r] = __expf(s[j][r] - m); sum += s[j][r]; }   // the hardware exponential: P is rounded to bfloat16 next
 #pragma unroll
     for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
     const float inv = 1.f / sum;

@@ -15,12 +15,7 @@ __device__ __forceinline__ void unpack8(const u32x4& w, float (&f)[8]) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
 }
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xFFFF0000u);
-}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_pack2(lo, hi); }
 __device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
   u32x4 o;
 #pragma unroll
@@ -28,11 +23,7 @@ __device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
   return o;
 }
 __device__ __forceinline__ float bf(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
-__device__ __forceinline__ uint16_t to_bf16(float v) {
-  uint32_t u = __float_as_uint(v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
+__device__ __forceinline__ uint16_t to_bf16(float v) { return bf16_round(v); }
 
 // Backward of z = scale * y + shift followed by an optional ReLU whose output is `act`:
 //   dz = dout * [act > 0]   (dz = dout without act);   dy = scale * dz;   dsum = dz (optional)
@@ -166,13 +157,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_bf16_kernel(const f32x4* __
     lo += partial[(size_t)z * slice_stride4 + 2 * j];
     hi += partial[(size_t)z * slice_stride4 + 2 * j + 1];
   }
-  auto pack = [](float a, float b) {
-    uint32_t x = __float_as_uint(a), y = __float_as_uint(b);
-    x += 0x7FFFu + ((x >> 16) & 1u);  // round to nearest, ties to even
-    y += 0x7FFFu + ((y >> 16) & 1u);
-    return (x >> 16) | (y & 0xFFFF0000u);
-  };
-  out[j] = make_uint4(pack(lo[0], lo[1]), pack(lo[2], lo[3]), pack(hi[0], hi[1]), pack(hi[2], hi[3]));
+  out[j] = make_uint4(bf16_pack2(lo[0], lo[1]), bf16_pack2(lo[2], lo[3]), bf16_pack2(hi[0], hi[1]), bf16_pack2(hi[2], hi[3]));
 }
 
 // 3x3 window, stride 2, padding 1 (acting as -inf); the first maximum in row-major window order wins.

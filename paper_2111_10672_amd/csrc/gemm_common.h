@@ -29,10 +29,7 @@ __device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float(((u
 
 __device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_elem(bf16_t* p, float v) {
-  // round to nearest, ties to even, on the upper 16 bits of the float32 pattern
-  uint32_t u = __float_as_uint(v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  p->bits = (uint16_t)(u >> 16);
+  p->bits = bf16_round(v);
 }
 
 struct GemmParams {

@@ -230,12 +230,7 @@ __device__ __forceinline__ void fragments_ready(u32x4 (&a)[NA], u32x4 (&b)[NB]) 
   for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
 }
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xFFFF0000u);
-}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return bf16_pack2(lo, hi); }
 
 // Epilogue.  Each wave parks 32 rows of its WM x WN accumulator tile at a time in its own LDS region (the tile
 // ring is dead by then) and reads them back row by row, so that bias, mask and result move in 16-byte pieces

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "bf16_round.h"
+
 namespace spb {
 
 enum class DType : int { F32 = 0, BF16 = 1 };

@@ -19,11 +19,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 __device__ __forceinline__ void store_dz(float* p, float v) { *p = v; }
-__device__ __forceinline__ void store_dz(uint16_t* p, float v) {
-  uint32_t u = __float_as_uint(v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  *p = (uint16_t)(u >> 16);
-}
+__device__ __forceinline__ void store_dz(uint16_t* p, float v) { *p = bf16_round(v); }
 
 // One workgroup of WAVES wavefronts per row when classes is large, one wavefront per row otherwise.
 template <typename DZ, int WAVES_PER_ROW>
@@ -78,10 +74,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kXentThreads = 512, kXentVecs = 16;   // rows of up to 512 * 16 * 4 = 32768 columns, pitch included
 __device__ __forceinline__ void store_dz4(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
 __device__ __forceinline__ void store_dz4(uint16_t* p, const f32x4& v) {
-  uint32_t u[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) { u[e] = __float_as_uint(v[e]); u[e] += 0x7FFFu + ((u[e] >> 16) & 1u); }
-  *reinterpret_cast<uint2*>(p) = make_uint2((u[0] >> 16) | (u[1] & 0xFFFF0000u), (u[2] >> 16) | (u[3] & 0xFFFF0000u));
+  *reinterpret_cast<uint2*>(p) = make_uint2(bf16_pack2(v[0], v[1]), bf16_pack2(v[2], v[3]));
 }
 template <typename DZ>
 __global__ __launch_bounds__(kXentThreads) void softmax_xent_long_kernel(const float* __restrict__ logits, int ldz,

@@ -28,23 +28,14 @@ __device__ __forceinline__ void unpack8(const u32x4& w, float (&f)[8]) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) { f[2 * d] = __uint_as_float(w[d] << 16); f[2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u); }
 }
-__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7FFFu + ((a >> 16) & 1u);  // round to nearest, ties to even
-  b += 0x7FFFu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xFFFF0000u);
-}
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) { return bf16_pack2(lo, hi); }
 __device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
   u32x4 o;
 #pragma unroll
   for (int d = 0; d < 4; ++d) o[d] = pack2(f[2 * d], f[2 * d + 1]);
   return o;
 }
-__device__ __forceinline__ uint16_t to_bf16(float v) {
-  uint32_t u = __float_as_uint(v);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
+__device__ __forceinline__ uint16_t to_bf16(float v) { return bf16_round(v); }
 
 // y[r] = gamma * (x[src(r)] - mean) * rstd + beta;  stats[r] = (mean, rstd).  src(r) = rows ? rows[r] : r.
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const uint16_t* __restrict__ x, int ldx, const int32_t* __restrict__ rows,
