@@ -15,3 +15,4 @@ autograd as a third opinion at full size.
 from .bf16 import round_to_bf16  # noqa: F401
 from .spb import spb_step, build_units, identity  # noqa: F401
 from .aggregate import aggregate_update, worker_depths, contributors  # noqa: F401
+from . import jigsaw  # noqa: F401
