@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--round-robin", action="store_true",
                     help="keep all five configurations resident and run their steps in turn: cost of switching between "
                          "models whose parameters stay on the device, and exit")
+    ap.add_argument("--jigsaw", action="store_true",
+                    help="time every (configuration, depth) pair on this GPU, build a seeded synthetic job mix from them and "
+                         "place it on a 45-device cluster task by task (Sec. 3) and as gangs, with and without SPB, and exit")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="run only a plain elementwise copy of this many MiB (10 launches) and exit: the reference "
                          "the HBM traffic counters are scaled by")
@@ -183,6 +186,65 @@ def round_robin(spb, torch, wl, reps):
                       "switching_overhead_ms": round(whole - sum(alone), 4), "resident_gb": round(resident / 1e9, 3)}))
 
 
+def jigsaw_report(spb, torch, wl, reps, n_jobs=200, n_machines=45, seed=0):
+    """Sec. 3-4.2: task-by-task placement of SPB jobs against gang scheduling of complete jobs, on a synthetic mix.
+    Every (configuration, depth) pair is timed on this GPU (step time and workspace: what the paper's scheduler
+    gets from profiling); jobs draw a configuration, a worker count with the paper's proportions (half the jobs
+    one worker, the rest 2 / 4 / 8 / 16 as 10 / 20 / 15 / 5 %) and an iteration count; worker j of W
+    backpropagates ceil(j L / W) units.  The cluster is `n_machines` copies of this GPU; moving a model costs its
+    parameter bytes at 50 GB/s.  The placement itself is the library's spb_schedule_tasks."""
+    import random
+    import time as _time
+    names = ["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"]
+    step_ms, ws_bytes, model_bytes, units = {}, {}, {}, {}
+    for n in names:
+        cfg = wl.get_config(n)
+        m = spb.SpbModel(cfg, wl.make_params(cfg, 0), "cuda:0")
+        b = {key: t.cuda() for key, t in wl.make_batch(cfg, 0).items()}
+        units[n] = m.n_units
+        m.reserve(m.n_units)
+        model_bytes[n] = sum(p.numel() * p.element_size() for p in m.params)
+        for k in range(1, m.n_units + 1):
+            for _ in range(2):
+                m.step(b, k)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                m.step(b, k)
+            e1.record()
+            torch.cuda.synchronize()
+            step_ms[(n, k)] = e0.elapsed_time(e1) / reps
+            ws_bytes[(n, k)] = spb.spb_workspace_size(m.handle, k)
+        m.close()
+    rng = random.Random(seed)
+    hbm = 288e9
+    jobs_spb, jobs_full = [], []
+    for _ in range(n_jobs):
+        n = rng.choice(names)
+        u = rng.random()
+        w = 1 if u < 0.5 else 2 if u < 0.6 else 4 if u < 0.8 else 8 if u < 0.95 else 16
+        iters = rng.randint(20, 120)
+        arrival = rng.uniform(0.0, 2.0)
+        depths = [-(-j * units[n] // w) for j in range(1, w + 1)]
+        common = dict(arrival=arrival, iterations=iters, model_size=float(model_bytes[n]))
+        jobs_spb.append(dict(common, durations=[step_ms[(n, k)] * 1e-3 for k in depths],
+                             resources=[ws_bytes[(n, k)] / hbm for k in depths]))
+        full = units[n]
+        jobs_full.append(dict(common, durations=[step_ms[(n, full)] * 1e-3] * w, resources=[ws_bytes[(n, full)] / hbm] * w))
+    gamma = 1.0 / 50e9
+    out = {"jobs": n_jobs, "machines": n_machines, "tasks": sum(len(j["durations"]) * j["iterations"] for j in jobs_spb)}
+    for label, jobs, gang in (("spb_tasks", jobs_spb, False), ("spb_gang", jobs_spb, True),
+                              ("full_tasks", jobs_full, False), ("full_gang", jobs_full, True)):
+        t0 = _time.perf_counter()
+        placed, makespan = spb.spb_schedule_tasks(jobs, n_machines, gamma=gamma, gang=gang)
+        out[label] = {"makespan_s": round(makespan, 4), "moved_fraction": round(sum(p["moved"] for p in placed) / max(1, len(placed)), 5),
+                      "placement_wall_s": round(_time.perf_counter() - t0, 3)}
+    out["makespan_ratio_spb_tasks_over_full_gang"] = round(out["spb_tasks"]["makespan_s"] / out["full_gang"]["makespan_s"], 4)
+    out["step_ms"] = {f"{n} k={k}": round(v, 4) for (n, k), v in step_ms.items()}
+    print(json.dumps(out))
+
+
 def server_update(spb, torch, wl, model, cfg, n_workers=4, reps=50):
     """The server side of an iteration (Sec. 2: per-layer average over the contributing workers, then the optimizer
     step) for 4 workers at depths ceil(j L / 4), timed outside the step's timed region: an HBM-bound kernel, reported
@@ -269,6 +331,9 @@ def main():
         return
     if args.round_robin:
         round_robin(spb, torch, wl, max(3, min(args.steps, 50)))
+        return
+    if args.jigsaw:
+        jigsaw_report(spb, torch, wl, max(3, min(args.steps, 20)))
         return
 
     cfg = wl.get_config(args.config)

@@ -219,6 +219,48 @@ int spb_read_kernel_timing(spb_model* m, spb_kernel_time* out, int32_t cap, int3
  * Errors: INVALID_ARG, STATE (no such product recorded), HIP. */
 int spb_replay_kernel(spb_model* m, const char* name, int32_t count, void* stream);
 
+/* ---- Placement of training tasks on devices and in time (Sec. 3, "Scheduling Algorithm") -------------------
+ * Host code only: no GPU is touched and every pointer below is a HOST pointer.
+ *
+ * A job is a chain of iterations; an iteration is one task per worker; the tasks of iteration i + 1 become
+ * ready when every task of iteration i of the same job has ended.  Under SPB the workers of a job differ in
+ * run time and memory, so tasks are placed one by one: ready tasks wait in a priority queue keyed by
+ * resource * duration (largest first; ties to the smaller job, iteration, worker), and the task taken from it
+ * goes to the device on which it can start earliest.  A device runs one task at a time and a task may fill a gap
+ * left between tasks placed before it.  On the device that ran the same worker in the previous iteration a task
+ * is ready when that iteration has ended; on any other device (and for a job's first iteration, on every device)
+ * gamma * model_size later, the time it takes to bring the model there.  Between devices that offer the same
+ * start the previous device wins, then the lowest index.
+ * gang != 0 gives the baseline the section compares with: the workers of an iteration start together, on as many
+ * devices, at the earliest time at which that many are free for the slowest worker's duration, and hold them
+ * that long; a worker keeps its previous device when that one is free then, the others take the free devices of
+ * lowest index and need the start-up delay; iterations are ordered by (sum of resources) * (slowest duration).
+ * (The paper normalises resource and duration by cluster constants, which does not change the order; what it
+ * leaves open - the tie rules, exclusive devices, the first iteration's delay - is as stated here.) */
+typedef struct spb_sched_job {
+  double arrival;           /* earliest start of the job's first iteration, >= 0 */
+  double model_size;        /* in the unit gamma is per, >= 0 */
+  int32_t iterations;       /* >= 0 */
+  int32_t workers;          /* >= 1 */
+  const double* durations;  /* [workers] run time of each worker's task, > 0 */
+  const double* resources;  /* [workers] GPU resource (e.g. peak memory) of each worker's task, in [0, capacity] */
+} spb_sched_job;
+
+typedef struct spb_sched_task {
+  int32_t job, iteration, worker;
+  int32_t machine;    /* device index in [0, n_machines) */
+  int32_t moved;      /* 1 when the previous iteration of this worker ran on another device */
+  double start, end;  /* the task computes during [start, end) */
+  double held_until;  /* its device is taken during [start, held_until): end, or the gang's end */
+} spb_sched_task;
+
+/* Places every task of every job.  out receives the tasks in the order in which they were placed (cap entries;
+ * n_out receives the number of tasks, also when cap is too small), makespan the latest held_until (0 without
+ * tasks).  Errors: INVALID_ARG (null pointer, a value outside the ranges above, n_machines < 1, a gang wider
+ * than the cluster, cap too small). */
+int spb_schedule_tasks(const spb_sched_job* jobs, int32_t n_jobs, int32_t n_machines, double gamma, double capacity,
+                       int32_t gang, spb_sched_task* out, int64_t cap, int64_t* n_out, double* makespan);
+
 #ifdef __cplusplus
 }
 #endif

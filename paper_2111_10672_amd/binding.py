@@ -48,6 +48,16 @@ class spb_kernel_time(C.Structure):
                 ("flops", C.c_double), ("bytes", C.c_double)]
 
 
+class spb_sched_job(C.Structure):
+    _fields_ = [("arrival", C.c_double), ("model_size", C.c_double), ("iterations", C.c_int32), ("workers", C.c_int32),
+                ("durations", C.POINTER(C.c_double)), ("resources", C.POINTER(C.c_double))]
+
+
+class spb_sched_task(C.Structure):
+    _fields_ = [("job", C.c_int32), ("iteration", C.c_int32), ("worker", C.c_int32), ("machine", C.c_int32),
+                ("moved", C.c_int32), ("start", C.c_double), ("end", C.c_double), ("held_until", C.c_double)]
+
+
 EXPORTS = {
     "spb_last_error": (C.c_char_p, []),
     "spb_model_create": (C.c_int, [C.POINTER(spb_model_desc), C.POINTER(C.c_void_p)]),
@@ -69,6 +79,8 @@ EXPORTS = {
     "spb_set_kernel_timing": (C.c_int, [C.c_void_p, C.c_int32]),
     "spb_replay_kernel": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int32, C.c_void_p]),
     "spb_read_kernel_timing": (C.c_int, [C.c_void_p, C.POINTER(spb_kernel_time), C.c_int32, C.POINTER(C.c_int32)]),
+    "spb_schedule_tasks": (C.c_int, [C.POINTER(spb_sched_job), C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_int32,
+                                     C.POINTER(spb_sched_task), C.c_int64, C.POINTER(C.c_int64), C.POINTER(C.c_double)]),
 }
 
 
@@ -231,6 +243,30 @@ def spb_read_kernel_timing(m, cap=1024):
     _check(lib().spb_read_kernel_timing(m, recs, cap, C.byref(n)))
     return [{"name": r.name.decode(), "launches": r.launches, "total_ms": r.total_ms, "flops": r.flops,
              "bytes": r.bytes} for r in recs[:n.value]]
+
+
+def spb_schedule_tasks(jobs, n_machines: int, gamma: float = 0.0, capacity: float = 1.0, gang: bool = False):
+    """jobs: list of dict(arrival, iterations, model_size, durations[w], resources[w]) -> (placements, makespan),
+    placements as dicts in the order the library placed them (host computation, no GPU)."""
+    arr = (spb_sched_job * max(1, len(jobs)))()
+    keep = []
+    total = 0
+    for a, job in zip(arr, jobs):
+        w = len(job["durations"])
+        if len(job["resources"]) != w:
+            raise ValueError("one duration and one resource per worker")
+        d = (C.c_double * max(1, w))(*[float(v) for v in job["durations"]])
+        r = (C.c_double * max(1, w))(*[float(v) for v in job["resources"]])
+        keep += [d, r]
+        a.arrival, a.model_size, a.iterations, a.workers = float(job["arrival"]), float(job["model_size"]), int(job["iterations"]), w
+        a.durations, a.resources = d, r
+        total += w * max(0, int(job["iterations"]))
+    out = (spb_sched_task * max(1, total))()
+    n, makespan = C.c_int64(), C.c_double()
+    _check(lib().spb_schedule_tasks(arr, len(jobs), int(n_machines), float(gamma), float(capacity), int(bool(gang)), out, total,
+                                    C.byref(n), C.byref(makespan)))
+    return ([dict(job=t.job, iteration=t.iteration, worker=t.worker, machine=t.machine, start=t.start, end=t.end,
+                  held_until=t.held_until, moved=bool(t.moved)) for t in out[:n.value]], makespan.value)
 
 
 class SpbModel:
