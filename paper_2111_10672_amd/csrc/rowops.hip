@@ -81,6 +81,61 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const uint16_t* __re
   if (lane == 0) { stats[2 * r] = mean; stats[2 * r + 1] = rstd; }
 }
 
+// The same forward pass for the widths that split evenly over lanes (LPR lanes per row, CPL 16-byte chunks per
+// lane): a wavefront takes 64 / LPR rows at once, every lane is busy, and scale and shift are requested together
+// with the row, not after the two reductions.
+template <int LPR, int CPL>
+__global__ __launch_bounds__(256) void layernorm_fwd_even_kernel(const uint16_t* __restrict__ x, int ldx, const int32_t* __restrict__ rows,
+                                                                 int n_rows, const uint16_t* __restrict__ gamma,
+                                                                 const uint16_t* __restrict__ beta, uint16_t* __restrict__ y, int ldy,
+                                                                 float* __restrict__ stats) {
+  constexpr int RPW = 64 / LPR, kWidth = LPR * CPL * 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int sub = lane / LPR, l = lane % LPR;
+  const int r = (blockIdx.x * 4 + wave) * RPW + sub;
+  const bool live = r < n_rows;
+  const int rc = live ? r : n_rows - 1;
+  const uint16_t* src = x + (size_t)(rows ? rows[rc] : rc) * ldx;
+  u32x4 xraw[CPL], graw[CPL], braw[CPL];
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    const int c = (l + LPR * i) * 8;
+    xraw[i] = *reinterpret_cast<const u32x4*>(src + c);
+    graw[i] = *reinterpret_cast<const u32x4*>(gamma + c);
+    braw[i] = *reinterpret_cast<const u32x4*>(beta + c);
+  }
+  float v[CPL][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    unpack8(xraw[i], v[i]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sum += v[i][e];
+  }
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+  const float mean = sum / (float)kWidth;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { const float d = v[i][e] - mean; sq += d * d; }
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+  const float rstd = rsqrtf(sq / (float)kWidth + kLnEps);
+  if (!live) return;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    float g[8], b[8], o[8];
+    unpack8(graw[i], g);
+    unpack8(braw[i], b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = g[e] * ((v[i][e] - mean) * rstd) + b[e];
+    *reinterpret_cast<u32x4*>(y + (size_t)r * ldy + (l + LPR * i) * 8) = pack8(o);
+  }
+  if (l == 0) { stats[2 * r] = mean; stats[2 * r + 1] = rstd; }
+}
+
 // LayerNorm backward for rows r0 .. r0+7 of this workgroup (2 per wavefront, so that the row loop is short and
 // a matrix of a few thousand rows still fills the chip):
 //   g = dy * gamma;  dx = (g - mean(g) - xhat * mean(g * xhat)) * rstd (+ res);  partial sums of dy * xhat and dy per column.
@@ -427,8 +482,20 @@ hipError_t launch_layernorm_fwd(const void* x, int ldx, const int32_t* rows, int
                                 void* y, int ldy, float* stats, hipStream_t s) {
   if (!x || !gamma || !beta || !y || !stats || n_rows <= 0 || !row_ok(width, ldx) || !row_ok(width, ldy)) return hipErrorInvalidValue;
   if (!a16(x) || !a16(y) || !a16(gamma) || !a16(beta)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, s, (const uint16_t*)x, ldx, rows, n_rows, width,
-                     (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)y, ldy, stats);
+  auto even = [&](auto kernel, int lpr) {
+    const int rows_per_block = 4 * (64 / lpr);
+    hipLaunchKernelGGL(kernel, dim3((n_rows + rows_per_block - 1) / rows_per_block), dim3(256), 0, s, (const uint16_t*)x, ldx, rows, n_rows,
+                       (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)y, ldy, stats);
+  };
+  const int chunks = width / 8;
+  if (chunks == 96) even(layernorm_fwd_even_kernel<32, 3>, 32);
+  else if (chunks == 64) even(layernorm_fwd_even_kernel<64, 1>, 64);
+  else if (chunks == 128) even(layernorm_fwd_even_kernel<64, 2>, 64);
+  else if (chunks == 16) even(layernorm_fwd_even_kernel<16, 1>, 16);
+  else if (chunks == 8) even(layernorm_fwd_even_kernel<8, 1>, 8);
+  else
+    hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((n_rows + 3) / 4), dim3(256), 0, s, (const uint16_t*)x, ldx, rows, n_rows, width,
+                       (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)y, ldy, stats);
   return hipGetLastError();
 }
 

@@ -58,6 +58,11 @@ CONFIGS = {
                                          ffn=256, vocab=97, loss_rows=31, depths=[0, 1, 2, 3, 4]),
     "fused_attention_short_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=1, hidden=64, heads=1,
                                        ffn=128, vocab=53, loss_rows=11, depths=[0, 1, 2, 3]),
+    # widths of 512 and 1024: the LayerNorm backward variants with one and two 16-byte chunks per lane
+    "wide_encoder_512_bf16": dict(family="encoder", dtype="bf16", batch=2, seq=24, layers=1, hidden=512, heads=8,
+                                  ffn=192, vocab=61, loss_rows=13, depths=[0, 1, 2, 3]),
+    "wide_encoder_1024_bf16": dict(family="encoder", dtype="bf16", batch=1, seq=40, layers=1, hidden=1024, heads=16,
+                                   ffn=128, vocab=37, loss_rows=9, depths=[0, 1, 2, 3]),
     "tiny_resnet_basic": dict(family="resnet_basic", dtype="bf16", batch=2, image=[6, 6, 3],
                               stem=dict(kernel=3, stride=1, pad=1, pool=False, width=4),
                               stage_blocks=[1, 1], stage_widths=[4, 6], classes=3, depths=[0, 1, 2, 3, 4]),
