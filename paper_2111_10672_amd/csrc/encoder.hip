@@ -252,19 +252,21 @@ class EncoderModel : public Model {
       // The previous layer's weight gradients read dF, dh and dqkv, which this layer is about to overwrite.
       if (int rc = join(s)) return rc;
       // feed-forward half
-      if (int rc = gemm(wgrad(dout, H, w + b.f, F, M, H, F, GP(W2W), GP(W2B)), fork(s))) return rc;
       {
         GemmProblem g = dgrad(dout, H, M, P(W2W), H, F, w + p.dF, F);   // dz1 = (dout W2) * gelu'(z1)
         g.epilogue = Epilogue::GeluBwdStore; g.mask = w + b.z1; g.ldmask = F;
         if (int rc = gemm(g, s)) return rc;
       }
-      if (int rc = gemm(wgrad(w + p.dF, F, w + b.v, H, M, F, H, GP(W1W), GP(W1B)), fork(s))) return rc;
+      {
+        hipStream_t side = fork(s);   // one fork for both weight gradients of the feed-forward half: each fork costs a few microseconds
+        if (int rc = gemm(wgrad(dout, H, w + b.f, F, M, H, F, GP(W2W), GP(W2B)), side)) return rc;
+        if (int rc = gemm(wgrad(w + p.dF, F, w + b.v, H, M, F, H, GP(W1W), GP(W1B)), side)) return rc;
+      }
       if (int rc = gemm(dgrad(w + p.dF, F, M, P(W1W), F, H, w + p.dv, H), s)) return rc;
       if (int rc = run("layernorm_bwd", 4 * mh, s, [&] {   // dh = dout + LN2 backward
             return launch_layernorm_bwd(w + p.dv, H, w + b.h, H, nullptr, reinterpret_cast<const float*>(w + b.stats2), P(LN2W), dout, H,
                                         w + p.dh, H, partial, GP(LN2W), GP(LN2B), M, H, s); })) return rc;
       // attention half
-      if (int rc = gemm(wgrad(w + p.dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), fork(s))) return rc;
       if (int rc = gemm(dgrad(w + p.dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
       const char* qbase = w + b.qkv;
       if (attention_fused_accepts(S, D, 3 * H, H)) {
@@ -297,7 +299,11 @@ class EncoderModel : public Model {
       if (int rc = attn_out("attn_bwd_dq", Layout::RowK, w + p.dscore, S, per_matrix(), bf(qbase, (size_t)H), 0)) return rc;
       if (int rc = attn_out("attn_bwd_dk", Layout::KRow, w + p.dscore, S, per_matrix(), qbase, 1)) return rc;
       }
-      if (int rc = gemm(wgrad(w + p.dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), fork(s))) return rc;
+      {
+        hipStream_t side = fork(s);   // and one for the attention half
+        if (int rc = gemm(wgrad(w + p.dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), side)) return rc;
+        if (int rc = gemm(wgrad(w + p.dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), side)) return rc;
+      }
       if (int rc = gemm(dgrad(w + p.dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
       void* dx = lowest ? nullptr : w + p.dx[which ^ 1];
       if (int rc = run("layernorm_bwd", (lowest ? 2 : 4) * mh, s, [&] {   // dx = dh + LN1 backward; the lowest unit forms no input gradient
