@@ -53,3 +53,24 @@ def test_two_stream_backward_gives_the_single_stream_bits(name):
                     assert torch.equal(eager[n], other[n]), f"{name} k={k}: {n} differs between eager and {how}"
     finally:
         model.close()
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_two_stream_backward_at_full_size(name):
+    """At full size the two streams' kernels really overlap on the chip (tens of microseconds each); a buffer handed
+    from one stream to the other too early shows up as a difference from the single-stream order."""
+    cfg = wl.get_config(name)
+    params, batch = wl.make_params(cfg, 0), wl.make_batch(cfg, 0)
+    model = spb.SpbModel(cfg, params)
+    try:
+        dev = {n: t.cuda() for n, t in batch.items()}
+        k = wl.depth_sweep(cfg)[-1]
+        print(f"case {name} k={k}", flush=True)
+        loss_a, serial = _grads(model, dev, k, "timed")
+        for rep in range(3):
+            loss_b, eager = _grads(model, dev, k, "eager")
+            assert loss_a == loss_b
+            for n in serial:
+                assert torch.equal(serial[n], eager[n]), f"{name} k={k} repetition {rep}: {n} differs"
+    finally:
+        model.close()
