@@ -849,7 +849,9 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   if (q.M >= 256 && t192 >= 176 && t192 <= 256 && (long)((q.N + 191) / 192) * 192 * 20 <= (long)q.N * 21)
     return launch_tile<256, 192, 2, 4, 2, LA, LB, GA, GB>(q, stream);
   const long t256 = tiles(256, 256);
-  if (q.M >= 256 && q.N >= 256 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
+  // (a k range of one or two tiles has nothing to reuse: such products are bound by memory and run better as two
+  // 128 x 128 workgroups per CU)
+  if (q.M >= 256 && q.N >= 256 && q.K > 128 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
   // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
   // alone on its CU needs a third stage in flight instead.
   if (tiles(128, 128) > 256) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
