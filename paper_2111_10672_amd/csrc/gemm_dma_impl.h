@@ -855,7 +855,12 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
   // alone on its CU needs a third stage in flight instead.
   if (tiles(128, 128) > 256) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
-  if (tiles(128, 128) >= 192) return launch_tile<128, 128, 3, 2, 2, LA, LB, GA, GB>(q, stream);
+  if (tiles(128, 128) >= 192) {
+    // one round of lone workgroups: convolutions (gathered operands) did 2-5 % better as two 128 x 64 workgroups per
+    // CU; plain products were level, and 128 x 128 leaves LDS for a weight-gradient workgroup of the second stream
+    if constexpr (GA != Gather::None || GB != Gather::None) return launch_tile<128, 64, 3, 4, 1, LA, LB, GA, GB>(q, stream);
+    else return launch_tile<128, 128, 3, 2, 2, LA, LB, GA, GB>(q, stream);
+  }
   // 64 x 64: the ring depth that lets every tile be resident at once (two or three workgroups per CU).
   if (tiles(64, 64) > 512) return launch_tile<64, 64, 3, 2, 2, LA, LB, GA, GB>(q, stream);
   return launch_tile<64, 64, 4, 2, 2, LA, LB, GA, GB>(q, stream);
