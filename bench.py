@@ -301,7 +301,7 @@ def cpu_baseline(cfg, params, batch, depths, budget_s):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs one worker's step on ONE GPU; no multi-GPU path exists. "
+        print("bench.py: the library runs one worker's step on ONE GPU; there is no multi-GPU path. "
               "Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
