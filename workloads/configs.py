@@ -49,6 +49,9 @@ CONFIGS = {
                            dims=[100, 72, 136, 52, 7], depths=[0, 1, 2, 3, 4]),
     "ragged_mlp_bf16": dict(family="mlp", dtype="bf16", batch=83,
                             dims=[136, 200, 72, 264, 13], depths=[0, 1, 2, 3, 4]),
+    # a perceptron with the matrix shapes of a Transformer layer at 4096 rows: the products go through the large
+    # tiles (256 x 192, 128 x 128 alone on a CU, 64 x 64 for the weight gradients) and are checked element by element
+    "wide_mlp_bf16": dict(family="mlp", dtype="bf16", batch=4096, dims=[768, 3072, 2304, 768, 24], depths=[2, 4]),
     "tiny_encoder": dict(family="encoder", dtype="bf16", batch=2, seq=4, layers=2, hidden=8, heads=2, ffn=16,
                          vocab=11, loss_rows=3, depths=[0, 1, 2, 3, 4]),
     "small_encoder_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=2, hidden=64, heads=4,
