@@ -58,19 +58,21 @@ def test_small_and_ragged_every_depth(name):
     _compare(cfg, 1, wl.unit_count(cfg), perturbed=False)
 
 
-def test_wide_perceptron_through_the_large_tiles():
-    """4096 rows against 768 / 3072 / 2304 columns: every product takes one of the large tiles.  The oracle runs
-    once, at full depth; gradients above a cut do not depend on the cut, so depth 2 is checked against the same."""
-    cfg = wl.get_config("wide_mlp_bf16")
+@pytest.mark.parametrize("name", ["wide_mlp_bf16", "big_tile_mlp_bf16"])
+def test_wide_perceptron_through_the_large_tiles(name):
+    """4096 rows against 768 / 3072 / 2304 columns, and 8192 x 4096 results: every product takes one of the large
+    tiles.  The oracle runs once, at full depth; gradients above a cut do not depend on the cut, so depth 2 is checked
+    against the same."""
+    cfg = wl.get_config(name)
     n_units = wl.unit_count(cfg)
     params, batch = wl.make_params(cfg, 0, True), wl.make_batch(cfg, 0)
-    print("case wide_mlp_bf16: oracle, exact", flush=True)
+    print(f"case {name}: oracle, exact", flush=True)
     _, exact = oracle.spb_step(cfg, params, batch, n_units)
-    print("case wide_mlp_bf16: oracle, bfloat16 storage", flush=True)
+    print(f"case {name}: oracle, bfloat16 storage", flush=True)
     ref_loss, ref = oracle.spb_step(cfg, params, batch, n_units, oracle.round_to_bf16)
     unit_of = {n: u for n, _s, u, _i in wl.tensor_specs(cfg)}
     for k in (n_units, 2):
-        print(f"case wide_mlp_bf16 k={k}", flush=True)
+        print(f"case {name} k={k}", flush=True)
         model, _, _ = _run(cfg, 0, k, True)
         try:
             assert abs(model.loss.item() - ref_loss) <= 5e-3 * abs(ref_loss)
