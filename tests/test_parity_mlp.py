@@ -50,7 +50,8 @@ def _compare(cfg, seed, k, perturbed=False):
         model.close()
 
 
-@pytest.mark.parametrize("name", ["tiny_mlp_f32", "ragged_mlp_f32", "ragged_mlp_bf16", "one_layer_bf16"])
+@pytest.mark.parametrize("name", ["tiny_mlp_f32", "ragged_mlp_f32", "ragged_mlp_bf16", "one_layer_bf16", "many_class_mlp_bf16",
+                                  "many_class_mlp_f32"])
 def test_small_and_ragged_every_depth(name):
     cfg = wl.get_config(name)
     for k in range(wl.unit_count(cfg) + 1):

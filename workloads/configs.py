@@ -54,6 +54,9 @@ CONFIGS = {
     "wide_mlp_bf16": dict(family="mlp", dtype="bf16", batch=4096, dims=[768, 3072, 2304, 768, 24], depths=[2, 4]),
     # 8192 x 4096 results over k = 512: 512 tiles of 256 x 256, several rounds over the CUs, forward and input gradient
     "big_tile_mlp_bf16": dict(family="mlp", dtype="bf16", batch=8192, dims=[512, 4096, 512, 16], depths=[2, 3]),
+    # several thousand classes: the loss kernel that keeps a whole row of logits in the registers of one workgroup
+    "many_class_mlp_bf16": dict(family="mlp", dtype="bf16", batch=37, dims=[72, 40, 4999], depths=[0, 1, 2]),
+    "many_class_mlp_f32": dict(family="mlp", dtype="f32", batch=21, dims=[36, 2050], depths=[0, 1]),
     "tiny_encoder": dict(family="encoder", dtype="bf16", batch=2, seq=4, layers=2, hidden=8, heads=2, ffn=16,
                          vocab=11, loss_rows=3, depths=[0, 1, 2, 3, 4]),
     "small_encoder_bf16": dict(family="encoder", dtype="bf16", batch=3, seq=40, layers=2, hidden=64, heads=4,
