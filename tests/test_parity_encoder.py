@@ -25,7 +25,7 @@ def _step(cfg, params, batch, k):
 
 
 @pytest.mark.parametrize("name", ["small_encoder_bf16", "fused_attention_encoder_bf16", "fused_attention_short_bf16",
-                                  "wide_encoder_512_bf16", "wide_encoder_1024_bf16"])
+                                  "wide_encoder_512_bf16", "wide_encoder_1024_bf16", "big_vocab_encoder_bf16"])
 @pytest.mark.parametrize("perturbed", [True, False])
 def test_small_encoder_every_depth(perturbed, name):
     cfg = wl.get_config(name)

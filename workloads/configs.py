@@ -71,6 +71,9 @@ CONFIGS = {
                                   ffn=192, vocab=61, loss_rows=13, depths=[0, 1, 2, 3]),
     "wide_encoder_1024_bf16": dict(family="encoder", dtype="bf16", batch=1, seq=40, layers=1, hidden=1024, heads=16,
                                    ffn=128, vocab=37, loss_rows=9, depths=[0, 1, 2, 3]),
+    # a vocabulary large enough for the head's input gradient to be cut into k-slices and for the long-row loss kernel
+    "big_vocab_encoder_bf16": dict(family="encoder", dtype="bf16", batch=2, seq=16, layers=1, hidden=64, heads=1,
+                                   ffn=72, vocab=2311, loss_rows=9, depths=[0, 1, 2, 3]),
     "tiny_resnet_basic": dict(family="resnet_basic", dtype="bf16", batch=2, image=[6, 6, 3],
                               stem=dict(kernel=3, stride=1, pad=1, pool=False, width=4),
                               stage_blocks=[1, 1], stage_widths=[4, 6], classes=3, depths=[0, 1, 2, 3, 4]),
