@@ -120,7 +120,7 @@ void place_gangs(const spb_sched_job* jobs, int n_jobs, int n_machines, double g
     weight[j] = sum * mx; slowest[j] = mx;
     if (q.iterations > 0) { release[j] = q.arrival; ready.insert(Key(-weight[j], j, 0)); }
   }
-  std::vector<double> candidates;
+  std::vector<double> candidates, earliest_gap;
   std::vector<int> assign, free_list;
   while (!ready.empty()) {
     const Key k = *ready.begin();
@@ -133,8 +133,15 @@ void place_gangs(const spb_sched_job* jobs, int n_jobs, int n_machines, double g
     for (const Device& dv : dev)
       for (auto it = dv.first_after(rel); it != dv.busy.end(); ++it) candidates.push_back(it->second);
     std::sort(candidates.begin(), candidates.end());
+    // Fewer than q.workers devices are free before the time by which that many have had their first gap of this
+    // length: earlier candidates cannot succeed and are not tried.
+    earliest_gap.clear();
+    for (const Device& dv : dev) earliest_gap.push_back(dv.earliest(rel, hold));
+    std::nth_element(earliest_gap.begin(), earliest_gap.begin() + (q.workers - 1), earliest_gap.end());
+    const double not_before = earliest_gap[q.workers - 1];
     double t_found = 0.0; bool found = false;
     for (double t : candidates) {
+      if (t < not_before) continue;
       free_list.clear();
       for (int m = 0; m < n_machines; ++m) if (dev[m].free_at(t, hold)) free_list.push_back(m);
       assign.assign(q.workers, -1);
