@@ -27,9 +27,9 @@ PEAK = {"mfma_bf16": 2500.0, "mfma_f32": 157.3, "hbm": 8000.0}   # TFLOP/s, TFLO
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=4000)
-    ap.add_argument("--warmup", type=int, default=400)
-    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing")
     ap.add_argument("--launch", choices=["auto", "graph", "eager"], default="auto",
@@ -57,22 +57,33 @@ def parse():
     return ap.parse_args()
 
 
-def measured_traffic(kernel_name):
-    """HBM bytes per launch of the roofline kernel from the stored counter readings (FETCH_SIZE and WRITE_SIZE,
-    scaled by a plain copy's readings), or None when there are none for this kernel or the kernel's sources have
-    changed since they were taken."""
+def stored_traffic(kernel_name):
+    """HBM bytes per launch of the roofline kernel from a counter summary kept under profiles/ (FETCH_SIZE and
+    WRITE_SIZE of two profiler passes, scaled by a plain copy's readings).  Such a file ends with `key = value`
+    lines: kernel, date, fetch_bytes_per_launch, write_bytes_per_launch, sources (file names under csrc/) and
+    sources_sha256.  Returns None when no file covers this kernel or the kernel's sources have changed since."""
+    import glob
     import hashlib
-    pkg = os.path.join(ROOT, "paper_2111_10672_amd")
-    try:
-        rec = json.load(open(os.path.join(pkg, "measured_traffic.json")))
-        h = hashlib.sha256()
-        for fn in rec["sources"]:
-            h.update(open(os.path.join(pkg, "csrc", fn), "rb").read())
-    except (OSError, KeyError, ValueError):
-        return None
-    if rec.get("kernel") != kernel_name or rec.get("sources_sha256") != h.hexdigest():
-        return None
-    return rec
+    csrc = os.path.join(ROOT, "paper_2111_10672_amd", "csrc")
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_hbm_traffic.txt"))):
+        rec = {}
+        try:
+            for line in open(path):
+                if " = " in line and not line.startswith(" "):
+                    key, val = line.split(" = ", 1)
+                    rec[key.strip()] = val.strip()
+            if rec.get("kernel") != kernel_name:
+                continue
+            h = hashlib.sha256()
+            for fn in rec["sources"].split():
+                h.update(open(os.path.join(csrc, fn), "rb").read())
+            if rec["sources_sha256"] != h.hexdigest():
+                continue
+            return {"file": os.path.relpath(path, ROOT), "date": rec.get("date"),
+                    "fetch": float(rec["fetch_bytes_per_launch"]), "write": float(rec["write_bytes_per_launch"])}
+        except (OSError, KeyError, ValueError):
+            continue
+    return None
 
 
 def table1(spb, torch, wl, reps):
@@ -274,14 +285,41 @@ def server_update(spb, torch, wl, model, cfg, n_workers=4, reps=50):
             "gbps": round(nbytes / us / 1e3, 1), "frac_hbm_peak": round(nbytes / us / 1e3 / PEAK["hbm"], 4)}
 
 
-def cpu_baseline(cfg, params, batch, depths, budget_s):
-    """The oracle as it stands, exact float64 mode, on this host's cores, on a bounded sample."""
+def cpu_model_name():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(wl, cfg, params, batch, depths, budget_s):
+    """The oracle as it stands, exact float64 mode, on this host's cores, on a bounded sample of the benchmarked
+    workload: whole depth sweeps for the perceptrons (milliseconds per step), ONE step at the deepest depth of the
+    sweep for the large configurations (tens of seconds; the bottleneck CNN on the first 8 images of its batch)."""
     import oracle
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
+    common = {"unit": "samples/s", "cores": int(cores), "kind": "oracle", "cpu": cpu_model_name()}
+    if cfg["family"] != "mlp":
+        k = depths[-1]
+        n = cfg["batch"]
+        if cfg["family"] == "resnet_bottleneck" and cfg["batch"] > 8:
+            n = 8
+            batch = {name: t[:n] for name, t in batch.items()}
+            cfg = dict(cfg, batch=n)
+        t0 = time.perf_counter()
+        oracle.spb_step(cfg, params, batch, k)
+        elapsed = time.perf_counter() - t0
+        return dict(common, value=n / elapsed, seconds=round(elapsed, 2),
+                    sample=f"{cfg['name']}: one step (full forward, backward through the top {k} units) on "
+                           f"{n} of the batch's {len(next(iter(batch.values()))) if n == cfg['batch'] else 64} samples, "
+                           f"float64 exact mode, {elapsed:.1f} s")
     oracle.spb_step(cfg, params, batch, depths[-1])            # touch everything once, untimed
     t0 = time.perf_counter()
     sweeps = 0
@@ -293,9 +331,39 @@ def cpu_baseline(cfg, params, batch, depths, budget_s):
         if elapsed >= budget_s or elapsed * (sweeps + 1) / sweeps > 2.5 * budget_s:
             break
     samples = sweeps * len(depths) * cfg["batch"]
-    return {"value": samples / elapsed, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{cfg['name']} full batch of {cfg['batch']}, {sweeps} sweep(s) over depths {depths}, "
-                      f"float64 exact mode, {elapsed:.1f} s"}
+    return dict(common, value=samples / elapsed, seconds=round(elapsed, 2),
+                sample=f"{cfg['name']} full batch of {cfg['batch']}, {sweeps} sweep(s) over depths {depths}, "
+                       f"float64 exact mode, {elapsed:.1f} s")
+
+
+RIDGE = {"bf16": PEAK["mfma_bf16"] * 1e3 / PEAK["hbm"], "f32": PEAK["mfma_f32"] * 1e3 / PEAK["hbm"]}   # flop per byte
+
+
+def is_backward_product(name):
+    return any(tag in name for tag in ("dgrad", "wgrad", "attn_bwd"))
+
+
+def product_roofline(rec, dtype, avg_us):
+    """One product class against the roofline that bounds it: the matrix-core peak when its arithmetic intensity
+    (flops over the bytes of each operand once plus the result once) is above the ridge, else that intensity times
+    the HBM peak.  Both fractions are given either way."""
+    mfma_peak = PEAK["mfma_f32" if dtype == "f32" else "mfma_bf16"]
+    flops, nbytes = rec["flops"] / rec["launches"], rec["bytes"] / rec["launches"]
+    ai = flops / nbytes
+    tflops = flops / avg_us / 1e6
+    gbps = nbytes / avg_us / 1e3
+    roof = min(mfma_peak, ai * PEAK["hbm"] / 1e3)          # TFLOP/s this product could reach at best
+    bound = "mfma" if ai >= RIDGE[dtype] else "hbm"
+    out = {"kernel": rec["name"], "bound": bound, "arithmetic_intensity_flop_per_byte": round(ai, 1),
+           "ridge_flop_per_byte": round(RIDGE[dtype], 1),
+           "tflops": round(tflops, 2), "frac_of_mfma_peak": round(tflops / mfma_peak, 5),
+           "frac_of_min_roof": round(tflops / roof, 5), "gbps_at_algorithmic_bytes": round(gbps, 1),
+           "flops_per_launch": flops, "algorithmic_bytes_per_launch": nbytes, "avg_launch_us": round(avg_us, 3)}
+    if bound == "mfma":
+        out.update(achieved=round(tflops, 3), peak=mfma_peak, unit="TFLOP/s", frac=round(tflops / mfma_peak, 5))
+    else:
+        out.update(achieved=round(gbps, 2), peak=PEAK["hbm"], unit="GB/s", frac=round(gbps / PEAK["hbm"], 5))
+    return out
 
 
 def main():
@@ -342,9 +410,8 @@ def main():
     model = spb.SpbModel(cfg, params, "cuda:0")
     dev = {n: t.cuda() for n, t in batch.items()}
     model.reserve(max(depths))
-    per_depth = max(1, -(-args.steps // len(depths)))
-    steps = per_depth * len(depths)
-    warm_per_depth = max(1, -(-args.warmup // len(depths)))
+    steps, warmup = max(1, args.steps), max(0, args.warmup)
+    sweep = lambda i: depths[i % len(depths)]      # step i runs at this depth: the sweep is walked step by step
 
     # One HIP graph per depth: the kernels of spb_forward(k) + spb_backward_truncated(k), nothing else.
     # (graph capture needs a stream of its own; eager launches stay on the default stream, the only one the
@@ -371,44 +438,53 @@ def main():
             with torch.cuda.graph(g, stream=stream):
                 model.step(dev, k)
             graphs[k] = g
-        for k in depths:
-            for _ in range(warm_per_depth):
-                graphs[k].replay()
+        for i in range(warmup):
+            graphs[sweep(i)].replay()
         stream.synchronize()
-        # ---- timed region: exactly `steps` steps -------------------------------------------------
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(len(depths) + 1)]
+        # ---- timed region: exactly `steps` steps, depths taken in turn ------------------------------
+        m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        marks[0].record(stream)
-        for i, k in enumerate(depths):
-            g = graphs[k]
-            for _ in range(per_depth):
-                g.replay()
-            marks[i + 1].record(stream)
+        m0.record(stream)
+        for i in range(steps):
+            graphs[sweep(i)].replay()
+        m1.record(stream)
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t0) * 1e3
+        total_ms = m0.elapsed_time(m1)
+
+        # ---- outside the timed region: each depth on its own (the sweep of the metric) ---------------
+        per_depth = max(2, min(200, -(-steps // len(depths))))
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(len(depths) + 1)]
+        marks[0].record(stream)
+        for i, k in enumerate(depths):
+            for _ in range(per_depth):
+                graphs[k].replay()
+            marks[i + 1].record(stream)
+        torch.cuda.synchronize()
         depth_ms = [marks[i].elapsed_time(marks[i + 1]) / per_depth for i in range(len(depths))]
-        total_ms = marks[0].elapsed_time(marks[-1])
 
         # ---- the same steps launched eagerly, every kernel bracketed by HIP events on this stream ----
-        timing_steps = max(2, min(200, per_depth))
+        timing_steps = max(2, min(50, per_depth))
         spb.spb_set_kernel_timing(model.handle, True)
         for _ in range(timing_steps):
             for k in depths:
                 model.step(dev, k)
         stream.synchronize()
         kernels = spb.spb_read_kernel_timing(model.handle)
-        # the product class with the largest total time, again: back-to-back copies between two events, which
-        # measures the kernel itself (the per-launch brackets above add about 2-3 us of event overhead each)
+        # The roofline kernel is the backward product (input gradient or weight gradient) with the largest total
+        # time.  Beside its in-step average (one event bracket per launch, which adds the dispatch latency of a
+        # few microseconds), the same product back-to-back between two events.
         products = [r for r in kernels if r["flops"] > 0]
-        dom_name = max(products or kernels, key=lambda r: r["total_ms"])["name"]
+        backward = [r for r in products if is_backward_product(r["name"])]
+        dom = max(backward or products or kernels, key=lambda r: r["total_ms"])
         back_to_back_us = None
-        if products:
-            reps = 200
-            spb.spb_replay_kernel(model.handle, dom_name, 20, stream.cuda_stream)
+        if dom["flops"] > 0:
+            reps = 100
+            spb.spb_replay_kernel(model.handle, dom["name"], 10, stream.cuda_stream)
             b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             b0.record(stream)
-            spb.spb_replay_kernel(model.handle, dom_name, reps, stream.cuda_stream)
+            spb.spb_replay_kernel(model.handle, dom["name"], reps, stream.cuda_stream)
             b1.record(stream)
             stream.synchronize()
             back_to_back_us = b0.elapsed_time(b1) * 1e3 / reps
@@ -416,54 +492,57 @@ def main():
 
     ms_per_step = total_ms / steps
     value = cfg["batch"] / (ms_per_step * 1e-3)
-    is_f32 = cfg["dtype"] == "f32"
-    mfma_peak = PEAK["mfma_f32" if is_f32 else "mfma_bf16"]
+    dtype = "f32" if cfg["dtype"] == "f32" else "bf16"
     table = []
     for r in kernels:
         avg_us = r["total_ms"] / r["launches"] * 1e3
-        table.append({"name": r["name"], "launches_per_sweep": r["launches"] / timing_steps, "avg_us": round(avg_us, 3),
-                      "tflops": round(r["flops"] / r["total_ms"] / 1e9, 3) if r["flops"] else None,
-                      "gbps": round(r["bytes"] / r["total_ms"] / 1e6, 2)})
-    dom = next(r for r in kernels if r["name"] == dom_name)
+        row = {"name": r["name"], "launches_per_sweep": r["launches"] / timing_steps, "avg_us": round(avg_us, 3),
+               "gbps": round(r["bytes"] / r["total_ms"] / 1e6, 2)}
+        if r["flops"]:
+            pr = product_roofline(r, dtype, avg_us)
+            row.update(tflops=pr["tflops"], bound=pr["bound"], frac_of_mfma_peak=pr["frac_of_mfma_peak"],
+                       frac_of_min_roof=pr["frac_of_min_roof"])
+        else:
+            row.update(bound="hbm", frac_of_hbm_peak=round(r["bytes"] / r["total_ms"] / 1e6 / PEAK["hbm"], 5))
+        table.append(row)
     if dom["flops"] > 0:
-        # note: the replayed product is the class's most recent launch; its flops are taken from that class's mean
-        flops_per_launch = dom["flops"] / dom["launches"]
-        achieved = flops_per_launch / back_to_back_us / 1e6       # TFLOP/s
-        rec = measured_traffic(dom["name"]) if args.config == "cfg2" else None
-        roofline = {"kernel": dom["name"], "bound": "mfma", "achieved": round(achieved, 3), "peak": mfma_peak,
-                    "unit": "TFLOP/s", "frac": round(achieved / mfma_peak, 5),
-                    "traffic": rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"] if rec else None,
-                    "traffic_unit": "HBM bytes per launch (fetch + write)",
-                    "traffic_fetch": rec["fetch_bytes_per_launch"] if rec else None,
-                    "traffic_write": rec["write_bytes_per_launch"] if rec else None,
-                    "algorithmic_bytes_per_launch": dom["bytes"] / dom["launches"],
-                    "avg_launch_us": round(back_to_back_us, 3),
-                    "avg_launch_us_event_bracketed": round(dom["total_ms"] / dom["launches"] * 1e3, 3),
-                    "flops_per_launch": flops_per_launch,
-                    "hbm_gbps_at_min_bytes": round(dom["bytes"] / dom["launches"] / back_to_back_us / 1e3, 2)}
+        roofline = product_roofline(dom, dtype, dom["total_ms"] / dom["launches"] * 1e3)
+        roofline["avg_launch_us_back_to_back"] = round(back_to_back_us, 3)
+        roofline["tflops_back_to_back"] = round(dom["flops"] / dom["launches"] / back_to_back_us / 1e6, 2)
+        rec = stored_traffic(dom["name"])
+        roofline["traffic"] = rec["fetch"] + rec["write"] if rec else None
+        if rec:
+            roofline.update(traffic_unit="HBM bytes per launch (fetch + write)", traffic_fetch=rec["fetch"], traffic_write=rec["write"],
+                            traffic_source=f"stored: {rec['file']} ({rec['date']}), kernel sources unchanged since")
     else:
         achieved = dom["bytes"] / dom["total_ms"] / 1e6
         roofline = {"kernel": dom["name"], "bound": "hbm", "achieved": round(achieved, 2), "peak": PEAK["hbm"],
                     "unit": "GB/s", "frac": round(achieved / PEAK["hbm"], 5), "traffic": None}
+    # all backward products together: flops over the summed in-step time
+    bwd_flops, bwd_ms = sum(r["flops"] for r in backward), sum(r["total_ms"] for r in backward)
+    shape = cfg["dims"] if "dims" in cfg else {k: cfg[k] for k in ("layers", "hidden", "heads", "ffn", "seq", "vocab", "loss_rows") if k in cfg} or \
+        {k: cfg[k] for k in ("image", "stage_blocks", "stage_widths", "classes")}
 
     out = {
         "metric": "SPB train-step samples/sec vs backprop depth k; % MFMA peak (bwd GEMMs)",
-        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": warm_per_depth * len(depths),
+        "value": round(value, 1), "unit": "samples/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if is_f32 else "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg['name']}: {cfg['family']} {cfg['dims'] if 'dims' in cfg else ''} batch {cfg['batch']}, "
-                               f"depth sweep k={depths}, steps shared evenly between depths",
-                   "launch": "eager" if eager else "hip_graph_replay", "steps_per_depth": per_depth},
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg['name']}: {cfg['family']} {shape} batch {cfg['batch']}, "
+                               f"depth sweep k={depths} walked step by step (step i runs depth number i mod {len(depths)})",
+                   "launch": "eager" if eager else "hip_graph_replay"},
         "samples_per_s_by_depth": {str(k): round(cfg["batch"] / (ms * 1e-3), 1) for k, ms in zip(depths, depth_ms)},
         "ms_by_depth": {str(k): round(ms, 6) for k, ms in zip(depths, depth_ms)},
         "workspace_bytes_by_depth": {str(k): spb.spb_workspace_size(model.handle, k) for k in depths},
         "wall_ms_timed_region": round(wall_ms, 3),
         "roofline": roofline,
-        "kernels": sorted(table, key=lambda r: -r["avg_us"] * r["launches_per_sweep"])[:16],
+        "backward_products_tflops": round(bwd_flops / bwd_ms / 1e9, 2) if bwd_ms else None,
+        "backward_products_frac_of_mfma_peak": round(bwd_flops / bwd_ms / 1e9 / PEAK["mfma_f32" if dtype == "f32" else "mfma_bf16"], 5) if bwd_ms else None,
+        "kernels": sorted(table, key=lambda r: -r["avg_us"] * r["launches_per_sweep"])[:24],
     }
     out["server_update"] = server_update(spb, torch, wl, model, cfg)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, params, batch, depths, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(wl, cfg, params, batch, depths, args.cpu_seconds)
     model.close()
     print(json.dumps(out))
 

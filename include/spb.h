@@ -147,7 +147,9 @@ int spb_workspace_size(const spb_model* m, int32_t k, size_t* bytes);
 /* Full forward pass to the loss (Sec. 2: every worker runs the whole forward pass), keeping only what a
  * backward pass of depth <= stash_depth_k will read.
  *   x          device, model dtype: [batch, dims[0]] (MLP), NHWC images (CNN); int32 token ids [batch, seq]
- *              in [0, vocab) (encoder).  The encoder reads the ids again in a full-depth backward pass.
+ *              in [0, vocab) (encoder).  Not copied: a backward pass of full depth (k = L) reads x again in every
+ *              family (the lowest unit's weight gradient needs its input; the encoder re-reads the ids), so x,
+ *              like labels and loss_rows, must stay unchanged until the matching backward call has completed.
  *   labels     device, int32, one class index per loss row, each in [0, classes)
  *   loss_rows  device, int32: the loss_rows distinct positions in [0, batch * seq) that carry a loss
  *              (encoder, read again by the backward pass); NULL otherwise

@@ -133,8 +133,9 @@ void KernelTimer::enable(bool on) { enabled_ = on; }
 void KernelTimer::get_events(hipEvent_t* a, hipEvent_t* b) {
   hipEvent_t* out[2] = {a, b};
   for (auto* o : out) {
+    *o = nullptr;
     if (!pool_.empty()) { *o = pool_.back(); pool_.pop_back(); }
-    else (void)hipEventCreate(o);
+    else if (hipEventCreate(o) != hipSuccess) { *o = nullptr; (void)hipGetLastError(); }
   }
 }
 
@@ -143,9 +144,19 @@ hipError_t KernelTimer::run(const char* name, double flops, double bytes, hipStr
   Rec r;
   r.name = name; r.flops = flops; r.bytes = bytes;
   get_events(&r.start, &r.stop);
-  (void)hipEventRecord(r.start, stream);
-  hipError_t e = launch();
-  (void)hipEventRecord(r.stop, stream);
+  if (!r.start || !r.stop) {                          // no events to be had: launch untimed rather than record garbage
+    if (r.start) pool_.push_back(r.start);
+    if (r.stop) pool_.push_back(r.stop);
+    return launch();
+  }
+  const hipError_t e0 = hipEventRecord(r.start, stream);
+  const hipError_t e = launch();
+  const hipError_t e1 = hipEventRecord(r.stop, stream);
+  if (e0 != hipSuccess || e1 != hipSuccess) {         // a bracket that was not recorded must not be read back later
+    pool_.push_back(r.start); pool_.push_back(r.stop);
+    (void)hipGetLastError();
+    return e != hipSuccess ? e : (e0 != hipSuccess ? e0 : e1);
+  }
   recs_.push_back(r);
   return e;
 }

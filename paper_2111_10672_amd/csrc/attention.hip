@@ -346,12 +346,7 @@ hipError_t launch_attention_fwd(const void* qkv, int ld_qkv, void* prob, void* c
                                 int head_dim, float scale, hipStream_t stream) {
   if (!qkv || !ctx || batch <= 0 || heads <= 0 || !attention_fused_accepts(seq, head_dim, ld_qkv, ld_ctx)) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(ctx) | reinterpret_cast<uintptr_t>(prob)) & 15) return hipErrorInvalidValue;
-  static bool raised = false;
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_fwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kAttnLds);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(attention_fwd_kernel), (size_t)kAttnLds); e != hipSuccess) return e;
   hipLaunchKernelGGL(attention_fwd_kernel, dim3(batch * heads), dim3(256), kAttnLds, stream, static_cast<const bf16_t*>(qkv), ld_qkv,
                      static_cast<bf16_t*>(prob), static_cast<bf16_t*>(ctx), ld_ctx, heads, seq, scale);
   return hipGetLastError();
@@ -362,12 +357,7 @@ hipError_t launch_attention_bwd(const void* qkv, int ld_qkv, const void* prob, c
   if (!qkv || !prob || !dctx || !dqkv || batch <= 0 || heads <= 0 || !attention_fused_accepts(seq, head_dim, ld_qkv, ld_ctx)) return hipErrorInvalidValue;
   if ((reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(prob) | reinterpret_cast<uintptr_t>(dctx) | reinterpret_cast<uintptr_t>(dqkv)) & 15)
     return hipErrorInvalidValue;
-  static bool raised = false;
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attention_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLds);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(attention_bwd_kernel), (size_t)kBwdLds); e != hipSuccess) return e;
   hipLaunchKernelGGL(attention_bwd_kernel, dim3(batch * heads), dim3(256), kBwdLds, stream, static_cast<const bf16_t*>(qkv), ld_qkv,
                      static_cast<const bf16_t*>(prob), static_cast<const bf16_t*>(dctx), ld_ctx, static_cast<bf16_t*>(dqkv), heads, seq, scale);
   return hipGetLastError();

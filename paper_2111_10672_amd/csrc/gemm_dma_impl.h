@@ -783,12 +783,7 @@ hipError_t launch_small(const GemmProblem& q, hipStream_t stream) {
   }
   constexpr size_t lds_bytes = small_product_lds(BM, BN, small_ring_depth(BM, BN, false));
   auto kernel = gemm_bf16_small_kernel<BM, BN, LA, LB>;
-  static bool raised = false;  // per instantiation
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes); e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(256), lds_bytes, stream, p);
   return hipGetLastError();
 }
@@ -806,14 +801,8 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
   constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kRowBytes;
   static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
   auto kernel = gemm_bf16_dma_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, LA, LB, GA, GB>;
-  if (lds_bytes > 64 * 1024) {
-    static bool raised = false;  // per instantiation
-    if (!raised) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-      if (e != hipSuccess) return e;
-      raised = true;
-    }
-  }
+  if (lds_bytes > 64 * 1024)
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes); e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
   return hipGetLastError();
 }

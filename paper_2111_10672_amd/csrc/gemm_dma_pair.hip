@@ -13,12 +13,7 @@ hipError_t launch_pair_tiles(const GemmProblem& d, const GemmProblem& w, hipStre
   auto kernel = gemm_bf16_small_pair_kernel<BM1, BN1, Layout::RowK, Layout::KRow, BM2, BN2, Layout::KRow, Layout::KRow>;
   constexpr size_t lds_bytes = small_pair_lds<BM1, BN1, BM2, BN2>();  // at most half a CU's LDS
   static_assert(lds_bytes <= 80 * 1024, "two workgroups per CU");
-  static bool raised = false;  // per instantiation
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), (size_t)lds_bytes); e != hipSuccess) return e;
   const int blocks = p1.tiles_m * p1.tiles_n + p2.tiles_m * p2.tiles_n;
   hipLaunchKernelGGL(kernel, dim3(blocks), dim3(256), lds_bytes, stream, p1, p2);
   return hipGetLastError();

@@ -200,12 +200,7 @@ hipError_t launch(const GemmProblem& q, hipStream_t stream) {
   const GemmParams p = make_params(q, 32, 32);
   constexpr size_t lds_bytes = (size_t)4 * kRing * kStage;  // 128 KiB; the parked partial tiles (18 KiB) overlay it
   auto kernel = gemm_f32_small_kernel<LA, LB>;
-  static bool raised = false;  // per instantiation
-  if (!raised) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), (size_t)lds_bytes); e != hipSuccess) return e;
   hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n), dim3(256), lds_bytes, stream, p);
   return hipGetLastError();
 }

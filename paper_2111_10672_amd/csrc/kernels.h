@@ -4,6 +4,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <map>
+#include <mutex>
+#include <utility>
+
 #include "bf16_round.h"
 
 namespace spb {
@@ -20,7 +24,7 @@ enum class Layout : int {
 
 enum class Epilogue : int {
   StoreF32 = 0,      // C float32 = alpha * acc (+ bias[n])
-  BiasAct = 1,       // v = alpha * acc + bias[n]; aux_out (T) = v if given; C (T) = act(v) (+ residual[m, n])
+  BiasAct = 1,       // v = alpha * acc * col_scale[n] + bias[n]; aux_out (T) = v if given; C (T) = act(v + residual[m, n])
   MaskStore = 2,     // C (T) = mask[m, n] > 0 ? acc : 0          (ReLU backward fused into the input-gradient product)
   GeluBwdStore = 3,  // C (T) = acc * gelu'(mask[m, n])           (GELU backward; mask holds the pre-activation)
 };
@@ -61,7 +65,7 @@ struct GemmProblem {
   int relu = 0;                   // shorthand for act = Relu
   Act act = Act::None;
   float alpha = 1.f;
-  const void* residual = nullptr; int ldres = 0;   // [M, N], dtype, added after the activation (BiasAct)
+  const void* residual = nullptr; int ldres = 0;   // [M, N], dtype, added to the biased value BEFORE the activation (BiasAct): C = act(v + residual)
   void* aux_out = nullptr; int ldaux = 0;          // [M, N], dtype, receives the pre-activation (BiasAct)
   const void* col_scale = nullptr;                 // [N], dtype: v = alpha * acc * col_scale[n] + bias[n]   (BiasAct)
   int aux_raw = 0;                                 // aux_out receives alpha * acc instead of the pre-activation
@@ -79,6 +83,23 @@ struct GemmProblem {
   float* a_row_sum = nullptr;     // optional [M]: sum_k A(m, k), written once by the tiles of column block 0
   const char* name = "gemm";
 };
+
+// A kernel that wants more than 64 KiB of dynamic LDS has to ask once.  The answer is kept per kernel (and per
+// device: each device has its own copy of the function), behind a lock: models on several host threads launch the
+// same instantiations.
+inline hipError_t raise_lds_limit(const void* kernel, size_t lds_bytes) {
+  static std::mutex lock;
+  static std::map<std::pair<const void*, int>, hipError_t> done;
+  int device = 0;
+  if (hipError_t e = hipGetDevice(&device); e != hipSuccess) return e;
+  std::lock_guard<std::mutex> guard(lock);
+  auto key = std::make_pair(kernel, device);
+  auto it = done.find(key);
+  if (it != done.end()) return it->second;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  if (e == hipSuccess) done.emplace(key, e);
+  return e;
+}
 
 // Checks shapes and alignment on the host, then enqueues one kernel.  Returns hipSuccess,
 // hipErrorInvalidValue for a problem the kernel cannot take, or the launch error.
