@@ -161,6 +161,26 @@ int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_
                 int32_t stash_depth_k, void* workspace, size_t workspace_bytes, float* loss_out,
                 void* stream);
 
+/* The same forward pass for callers that cannot allocate and have no workspace to hand over (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is a device array of
+ * SPB_STATIC_WORKSPACE_BYTES that the library holds itself (one copy on every GPU it runs on, until the process
+ * ends), and the call creates no stream, event or buffer.  Arguments as spb_forward, without the workspace; the
+ * matching spb_backward_truncated then reads that array.  Differences from spb_forward:
+ *   - a depth whose spb_workspace_size exceeds SPB_STATIC_WORKSPACE_BYTES is refused with SPB_ERR_WORKSPACE
+ *     before anything is enqueued (the two perceptron workloads fit at every depth; the CNN and encoder
+ *     workloads at full size do not);
+ *   - the model's second stream is not created here, so unless an earlier spb_forward created it the backward
+ *     pass stays on the caller's stream (same bits either way);
+ *   - all models and all calls on one GPU share the one array, which keeps the last call's contents: a step
+ *     (this call up to the end of its backward pass) must have completed on the device before the next
+ *     spb_forward_static on that GPU is enqueued on another stream, or the two race.  Nothing needs to start at
+ *     zero: every kernel writes what it later reads, pad columns included;
+ *   - the first call on a device looks up the array's address and is best made outside a stream capture.
+ * Errors: INVALID_ARG, DEPTH_RANGE, STATE, WORKSPACE (does not fit), HIP. */
+#define SPB_STATIC_WORKSPACE_BYTES (8u << 20)
+int spb_forward_static(spb_model* m, const void* x, const int32_t* labels, const int32_t* loss_rows,
+                       int32_t stash_depth_k, float* loss_out, void* stream);
+
 /* Backward pass over the top k units only (Sec. 2: a worker backpropagates a fixed suffix of the network
  * that starts at the output layer).  Requires a preceding spb_forward with
  * stash_depth_k >= k on the same workspace.  Overwrites (does not accumulate into) the gradient

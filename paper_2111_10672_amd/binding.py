@@ -70,6 +70,7 @@ EXPORTS = {
     "spb_workspace_size": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]),
     "spb_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p,
                               C.c_size_t, C.c_void_p, C.c_void_p]),
+    "spb_forward_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "spb_backward_truncated": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "spb_grad_buffers": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spb_grad_view), C.c_int32, C.POINTER(C.c_int32)]),
     "spb_zero_absent_grads": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
@@ -198,6 +199,13 @@ def spb_forward(m, x, labels, loss_rows, k, workspace, workspace_bytes, loss_out
                              workspace_bytes, _ptr(loss_out), C.c_void_p(stream)))
 
 
+SPB_STATIC_WORKSPACE_BYTES = 8 << 20
+
+
+def spb_forward_static(m, x, labels, loss_rows, k, loss_out, stream):
+    _check(lib().spb_forward_static(m, _ptr(x), _ptr(labels), _ptr(loss_rows), k, _ptr(loss_out), C.c_void_p(stream)))
+
+
 def spb_backward_truncated(m, k, stream):
     _check(lib().spb_backward_truncated(m, k, C.c_void_p(stream)))
 
@@ -309,6 +317,10 @@ class SpbModel:
         self.reserve(k)
         spb_forward(self.handle, batch["x"], batch["labels"], batch.get("loss_rows"), k, self.workspace,
                     self.workspace_bytes, self.loss, self.stream())
+
+    def forward_static(self, batch: dict, k: int):
+        """The forward pass on the library's own fixed-size workspace (allocates nothing)."""
+        spb_forward_static(self.handle, batch["x"], batch["labels"], batch.get("loss_rows"), k, self.loss, self.stream())
 
     def backward(self, k: int):
         spb_backward_truncated(self.handle, k, self.stream())

@@ -4,6 +4,7 @@
 
 #include <cstring>
 #include <map>
+#include <mutex>
 
 namespace spb {
 
@@ -296,6 +297,65 @@ int spb_forward(spb_model* m, const void* x, const int32_t* labels, const int32_
   SPB_REQUIRE(workspace && workspace_bytes >= need, SPB_ERR_WORKSPACE, "spb_forward: workspace of %zu bytes, depth %d needs %zu", workspace_bytes, k, need);
   SPB_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255u) == 0, SPB_ERR_WORKSPACE, "spb_forward: workspace is not 256-byte aligned");
   m->impl->ensure_side_stream(static_cast<hipStream_t>(stream));
+  int rc = m->impl->forward(x, labels, loss_rows, k, workspace, loss_out, static_cast<hipStream_t>(stream));
+  if (rc != SPB_OK) return rc;
+  m->impl->stashed_k = k;
+  m->impl->ws = workspace;
+  return SPB_OK;
+}
+
+// ---- forward pass on a workspace the library holds itself ---------------------------------------------------
+// For callers that may not allocate (code under stream capture, tight serving loops): the workspace is a
+// file-scope device array of fixed size instead of a caller buffer, and nothing on this path allocates (no
+// stream, no event, no device memory).  Every device the library runs on has its own copy of the array; its
+// address on a device is looked up once, with that device current.
+static __device__ __align__(256) unsigned char scratch[SPB_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch` (never the array's name: in host code that is a stand-in).
+int static_workspace(void** out) {
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) {
+    (void)hipGetLastError();
+    set_error("spb_forward_static: cannot tell the current device");
+    return SPB_ERR_HIP;
+  }
+  std::lock_guard<std::mutex> guard(g_scratch_lock);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      set_error("spb_forward_static: address of the static workspace on device %d: %s", device, hipGetErrorString(e));
+      return SPB_ERR_HIP;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return SPB_OK;
+}
+}  // namespace
+
+int spb_forward_static(spb_model* m, const void* x, const int32_t* labels, const int32_t* loss_rows, int32_t k,
+                       float* loss_out, void* stream) {
+  SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_forward_static: null model");
+  m->impl->stashed_k = -1;
+  SPB_REQUIRE(x && labels && loss_out, SPB_ERR_INVALID_ARG, "spb_forward_static: null input, labels or loss pointer");
+  SPB_REQUIRE(!m->impl->needs_loss_rows || loss_rows, SPB_ERR_INVALID_ARG, "spb_forward_static: this model needs the loss_rows index array");
+  SPB_REQUIRE((reinterpret_cast<uintptr_t>(x) & 15u) == 0, SPB_ERR_INVALID_ARG, "spb_forward_static: input is not 16-byte aligned");
+  if (int rc = depth_ok(m, k, "spb_forward_static")) return rc;
+  SPB_REQUIRE(m->impl->params_bound, SPB_ERR_STATE, "spb_forward_static: parameters are not bound");
+  const size_t need = m->impl->workspace_size(k);
+  SPB_REQUIRE(need <= (size_t)SPB_STATIC_WORKSPACE_BYTES, SPB_ERR_WORKSPACE,
+              "spb_forward_static: depth %d needs a workspace of %zu bytes, the static one holds %zu", k, need, (size_t)SPB_STATIC_WORKSPACE_BYTES);
+  void* workspace = nullptr;
+  if (int rc = static_workspace(&workspace)) return rc;
+  // no ensure_side_stream here: creating a stream and events would allocate.  Without one (or while `stream` is
+  // being captured) the backward pass keeps everything on the caller's stream.
   int rc = m->impl->forward(x, labels, loss_rows, k, workspace, loss_out, static_cast<hipStream_t>(stream));
   if (rc != SPB_OK) return rc;
   m->impl->stashed_k = k;
