@@ -195,6 +195,28 @@ int spb_backward_truncated(spb_model* m, int32_t k, void* stream);
  * Errors: DEPTH_RANGE, INVALID_ARG (cap too small), STATE (gradients not bound). */
 int spb_grad_buffers(const spb_model* m, int32_t k, spb_grad_view* out, int32_t cap, int32_t* n_out);
 
+/* Read-only description of two tensors a step leaves in the caller's workspace, for tests and diagnosis that check
+ * one unit at a time (Sec. 1: the gradient of a layer depends only on the layers after it, so a unit's backward
+ * pass is fixed by the unit's input and the gradient entering it from above).  Host-only; nothing is enqueued.
+ *   input        where a forward pass with stash depth k keeps the INPUT of unit `unit` (unit >= L - k)
+ *   output_grad  where the gradient of the loss with respect to the unit's OUTPUT lies after
+ *                spb_backward_truncated of depth exactly L - unit, i.e. with `unit` the lowest visited unit (a deeper
+ *                backward pass reuses the buffer).  offset = SPB_VIEW_NONE for the top unit, which carries the loss.
+ * A view is row-major [rows, cols] with `pitch` elements from row to row (NHWC tensors: rows = pixels, cols =
+ * channels); offset is in bytes from the workspace base, or SPB_VIEW_CALLER_INPUT when the tensor is the x the
+ * caller passed (unit 0), or SPB_VIEW_NONE.  relu_applied = 1 on a perceptron unit's output_grad: the mask of the
+ * unit's own ReLU is already applied (it is the gradient at the unit's pre-activation).
+ * Errors: DEPTH_RANGE, INVALID_ARG (unit below the cut of depth k). */
+#define SPB_VIEW_CALLER_INPUT (-1)
+#define SPB_VIEW_NONE (-2)
+typedef struct spb_buffer_view {
+  int64_t offset;
+  int64_t rows, cols, pitch;
+  int32_t dtype;         /* SPB_DTYPE_* */
+  int32_t relu_applied;
+} spb_buffer_view;
+int spb_unit_io(const spb_model* m, int32_t stash_depth_k, int32_t unit, spb_buffer_view* input, spb_buffer_view* output_grad);
+
 /* Fill with zeros the gradient buffers of the units below the cut, for callers that want dense
  * gradients.  Buffers bound as NULL are skipped. */
 int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream);

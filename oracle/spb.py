@@ -141,7 +141,7 @@ class EncoderLayerUnit:
         v, self.ln2 = ops.layernorm_fwd(self.h, P("ln2.weight"), P("ln2.bias"))
         self.v = q(v)
         z1 = ops.linear_fwd(self.v, P("ffn.w1.weight"), P("ffn.w1.bias"))
-        self.z1 = q(z1)                      # kept for the GELU derivative
+        self.dgelu = q(ops.gelu_grad(z1))    # what a path keeps of z1 for the backward pass: the GELU derivative itself
         self.f = q(ops.gelu_fwd(z1))
         return q(self.h + ops.linear_fwd(self.f, P("ffn.w2.weight"), P("ffn.w2.bias")))
 
@@ -151,7 +151,7 @@ class EncoderLayerUnit:
         hidden = dout.shape[1]
         # feed-forward half
         g[self.pre + "ffn.w2.weight"], g[self.pre + "ffn.w2.bias"], df = ops.linear_bwd(dout, self.f, P("ffn.w2.weight"), True)
-        dz1 = q(df * ops.gelu_grad(self.z1))
+        dz1 = q(df * self.dgelu)
         g[self.pre + "ffn.w1.weight"], g[self.pre + "ffn.w1.bias"], dv = ops.linear_bwd(dz1, self.v, P("ffn.w1.weight"), True)
         dv = q(dv)
         dh_ln, g[self.pre + "ln2.weight"], g[self.pre + "ln2.bias"] = ops.layernorm_bwd(dv, P("ln2.weight"), self.ln2)

@@ -43,6 +43,11 @@ class spb_grad_view(C.Structure):
     _fields_ = [("param_index", C.c_int32), ("unit", C.c_int32), ("data", C.c_void_p), ("numel", C.c_int64)]
 
 
+class spb_buffer_view(C.Structure):
+    _fields_ = [("offset", C.c_int64), ("rows", C.c_int64), ("cols", C.c_int64), ("pitch", C.c_int64),
+                ("dtype", C.c_int32), ("relu_applied", C.c_int32)]
+
+
 class spb_kernel_time(C.Structure):
     _fields_ = [("name", C.c_char * SPB_NAME_LEN), ("launches", C.c_int64), ("total_ms", C.c_double),
                 ("flops", C.c_double), ("bytes", C.c_double)]
@@ -73,6 +78,7 @@ EXPORTS = {
     "spb_forward_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
     "spb_backward_truncated": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "spb_grad_buffers": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(spb_grad_view), C.c_int32, C.POINTER(C.c_int32)]),
+    "spb_unit_io": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(spb_buffer_view), C.POINTER(spb_buffer_view)]),
     "spb_zero_absent_grads": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p]),
     "spb_worker_depth": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]),
     "spb_aggregate_update": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
@@ -218,6 +224,18 @@ def spb_grad_buffers(m, k, cap=None):
     return [{"param_index": v.param_index, "unit": v.unit, "data": v.data, "numel": v.numel} for v in views[:n.value]]
 
 
+SPB_VIEW_CALLER_INPUT, SPB_VIEW_NONE = -1, -2
+
+
+def spb_unit_io(m, k: int, unit: int):
+    """(input view, output-gradient view) of a unit as dicts; see spb.h."""
+    a, b = spb_buffer_view(), spb_buffer_view()
+    _check(lib().spb_unit_io(m, k, unit, C.byref(a), C.byref(b)))
+    as_dict = lambda v: {"offset": v.offset, "rows": v.rows, "cols": v.cols, "pitch": v.pitch,
+                         "dtype": {0: "f32", 1: "bf16", 2: "i32"}[v.dtype], "relu_applied": bool(v.relu_applied)}
+    return as_dict(a), as_dict(b)
+
+
 def spb_zero_absent_grads(m, k, stream):
     _check(lib().spb_zero_absent_grads(m, k, C.c_void_p(stream)))
 
@@ -337,6 +355,20 @@ class SpbModel:
             assert g.data_ptr() == v["data"] and g.numel() == v["numel"]
             out[self.infos[v["param_index"]]["name"]] = g
         return out
+
+    def read_view(self, view: dict, batch: dict = None):
+        """The tensor a spb_unit_io view describes, copied out of the workspace as a float64 (ids: int64) CPU tensor
+        [rows, cols]; None for SPB_VIEW_NONE."""
+        torch = self.torch
+        if view["offset"] == SPB_VIEW_NONE:
+            return None
+        if view["offset"] == SPB_VIEW_CALLER_INPUT:
+            x = batch["x"].detach().cpu()
+            return x.reshape(view["rows"], -1).long() if view["dtype"] == "i32" else x.reshape(view["rows"], -1).double()
+        tdtype, size = {"f32": (torch.float32, 4), "bf16": (torch.bfloat16, 2)}[view["dtype"]]
+        nbytes = ((view["rows"] - 1) * view["pitch"] + view["cols"]) * size
+        raw = self.workspace[view["offset"]:view["offset"] + nbytes].view(tdtype)
+        return torch.as_strided(raw, (view["rows"], view["cols"]), (view["pitch"], 1)).double().cpu()
 
     def close(self):
         if self.handle is not None:

@@ -408,6 +408,15 @@ int spb_grad_buffers(const spb_model* m, int32_t k, spb_grad_view* out, int32_t 
   return SPB_OK;
 }
 
+int spb_unit_io(const spb_model* m, int32_t k, int32_t unit, spb_buffer_view* input, spb_buffer_view* output_grad) {
+  SPB_REQUIRE(m && input && output_grad, SPB_ERR_INVALID_ARG, "spb_unit_io: null argument");
+  if (int rc = depth_ok(m, k, "spb_unit_io")) return rc;
+  const int L = m->impl->num_units;
+  SPB_REQUIRE(unit >= L - k && unit < L, SPB_ERR_INVALID_ARG, "spb_unit_io: unit %d is not among the top %d of %d units", unit, k, L);
+  m->impl->unit_io(k, unit, input, output_grad);
+  return SPB_OK;
+}
+
 int spb_zero_absent_grads(spb_model* m, int32_t k, void* stream) {
   SPB_REQUIRE(m, SPB_ERR_INVALID_ARG, "spb_zero_absent_grads: null model");
   if (int rc = depth_ok(m, k, "spb_zero_absent_grads")) return rc;

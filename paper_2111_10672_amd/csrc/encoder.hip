@@ -5,7 +5,7 @@
 //           v = LN2(h);  z1 = v W1^T + b1;  f = gelu(z1);  out = h + f W2^T + b2
 //   head:   y = LN(x[loss rows]);  logits = y Wv^T + bv;  mean softmax cross-entropy
 //
-// A layer above the cut keeps u, qkv, P, ctx, h, v, z1, f and the LayerNorm statistics; layers below the
+// A layer above the cut keeps u, qkv, P, ctx, h, v, gelu'(z1), f and the LayerNorm statistics; layers below the
 // cut share one scratch set and their outputs alternate between two buffers.  Every product runs on the
 // MFMA kernel of gemm_dma.hip (attention as batched products over batch x heads); bias, GELU, residual
 // adds and the GELU derivative ride in its epilogue, the residual fan-in of the backward pass rides in the
@@ -180,7 +180,8 @@ class EncoderModel : public Model {
             return launch_layernorm_fwd(w + b.h, H, nullptr, M, H, P(LN2W), P(LN2B), w + b.v, H, reinterpret_cast<float*>(w + b.stats2), s); })) return rc;
       {
         GemmProblem g = linear(w + b.v, H, M, P(W1W), F, H, P(W1B), w + b.f, F);
-        g.act = Act::Gelu; g.aux_out = w + b.z1; g.ldaux = F;
+        g.act = Act::Gelu;
+        if (i + 1 >= num_units - k) { g.aux_out = w + b.z1; g.ldaux = F; g.aux_act_grad = 1; }   // above the cut: keep gelu'(z1), all the backward pass needs of z1
         if (int rc = gemm(g, s)) return rc;
       }
       {
@@ -253,8 +254,8 @@ class EncoderModel : public Model {
       if (int rc = join(s)) return rc;
       // feed-forward half
       {
-        GemmProblem g = dgrad(dout, H, M, P(W2W), H, F, w + p.dF, F);   // dz1 = (dout W2) * gelu'(z1)
-        g.epilogue = Epilogue::GeluBwdStore; g.mask = w + b.z1; g.ldmask = F;
+        GemmProblem g = dgrad(dout, H, M, P(W2W), H, F, w + p.dF, F);   // dz1 = (dout W2) * gelu'(z1), the factor as stashed
+        g.epilogue = Epilogue::ScaleStore; g.mask = w + b.z1; g.ldmask = F;
         if (int rc = gemm(g, s)) return rc;
       }
       {
@@ -316,6 +317,18 @@ class EncoderModel : public Model {
     if (cut == 0)
       return run("embedding_bwd", mh + (double)V * H * 4, s, [&] { return launch_embedding_bwd(ids_, dout, H, G(0), G(1), B, S, V, H, s); });
     return SPB_OK;
+  }
+
+  void unit_io(int k, int unit, spb_buffer_view* input, spb_buffer_view* output_grad) const override {
+    const Plan p = plan(k);
+    if (unit == 0) {
+      *input = make_view(SPB_VIEW_CALLER_INPUT, B, S, S, DType::F32);
+      input->dtype = SPB_DTYPE_I32;   // token ids
+    } else {
+      *input = make_view((long long)p.xout[unit - 1], M, H, H, dtype);
+    }
+    // The head writes the gradient of the last layer's output into dx[0]; each layer reads one and writes the other.
+    *output_grad = (unit == NL + 1 || k < 2) ? no_view() : make_view((long long)p.dx[(NL - unit) & 1], M, H, H, dtype);
   }
 
  private:

@@ -37,7 +37,7 @@ struct GemmParams {
   const void* bias; const void* mask; float* a_row_sum;
   const void* residual; void* aux_out; const void* col_scale;
   int M, N, K, lda, ldb, ldc, ldmask, ldres, ldaux;
-  int epilogue, act, aux_raw;
+  int epilogue, act, aux_raw, aux_act_grad;
   float alpha;
   int k_tiles_per_split;  // 0: blockIdx.y is a batch entry; > 0: blockIdx.y is a slice of the k range
   ConvGeom conv;
@@ -69,14 +69,14 @@ __device__ __forceinline__ float gelu_f(float x) {
   const float erf_u = copysignf(fmaf(-pt, e, 1.f), x);
   return 0.5f * x * (1.f + erf_u);
 }
-// d/dx gelu(x) = Phi(x) + x phi(x); exp(-u^2) with u = x / sqrt(2) is the exponential of both terms.
-__device__ __forceinline__ float gelu_grad_f(float x) {
+// gelu(x) and gelu'(x) from one evaluation of the erf formula (the forward epilogue that stashes the derivative).
+__device__ __forceinline__ void gelu_both_f(float x, float& y, float& dy) {
   float pt, e;
   erf_parts(fabsf(x) * 0.70710678118654752f, pt, e);
-  const float erf_u = copysignf(fmaf(-pt, e, 1.f), x);
-  return fmaf(x * 0.3989422804014327f, e, 0.5f * (1.f + erf_u));
+  const float cdf = 0.5f * (1.f + copysignf(fmaf(-pt, e, 1.f), x));
+  y = x * cdf;
+  dy = fmaf(x * 0.3989422804014327f, e, cdf);
 }
-
 
 // Accumulator register r of lane l of a 32x32 MFMA block holds C[8*(r/4) + 4*(l/32) + r%4][l%32].
 template <typename T, int TM, int TN>
@@ -116,7 +116,7 @@ inline GemmParams make_params(const GemmProblem& q, int bm, int bn) {
   p.M = q.M; p.N = q.N; p.K = q.K; p.lda = q.lda; p.ldb = q.ldb; p.ldc = q.ldc; p.ldmask = q.ldmask;
   p.residual = q.residual; p.aux_out = q.aux_out; p.ldres = q.ldres; p.ldaux = q.ldaux;
   p.epilogue = (int)q.epilogue; p.act = q.relu ? (int)Act::Relu : (int)q.act;
-  p.alpha = q.alpha; p.col_scale = q.col_scale; p.aux_raw = q.aux_raw;
+  p.alpha = q.alpha; p.col_scale = q.col_scale; p.aux_raw = q.aux_raw; p.aux_act_grad = q.aux_act_grad;
   p.conv = q.conv;
   p.k_tiles_per_split = 0;
   p.a_batch = q.a_batch; p.b_batch = q.b_batch; p.c_batch = q.c_batch;

@@ -38,7 +38,7 @@ bool gemm_dma_accepts(const GemmProblem& p) {
   const int per_out = p.epilogue == Epilogue::StoreF32 ? 4 : 8;
   if (p.ldc % per_out || !a16(p.C)) return false;
   if (p.bias && !a16(p.bias)) return false;
-  const bool reads_mask = p.epilogue == Epilogue::MaskStore || p.epilogue == Epilogue::GeluBwdStore;
+  const bool reads_mask = p.epilogue == Epilogue::MaskStore || p.epilogue == Epilogue::ScaleStore;
   if (reads_mask && (!p.mask || p.ldmask % 8 || !a16(p.mask))) return false;
   if (p.residual && (p.ldres % 8 || !a16(p.residual))) return false;
   if (p.aux_out && (p.ldaux % 8 || !a16(p.aux_out))) return false;

@@ -241,7 +241,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return bf16_
 // All bfloat16 epilogues are one formula per element,
 //     out = act(alpha * acc * s + b + r),
 // with s, b per column and r per element:  BiasAct: s = column scale or 1, b = bias or 0, r = residual or 0;
-// MaskStore: s = [x > 0]; GeluBwdStore: s = gelu'(x), where x is the per-element tensor `mask`.  At most one
+// MaskStore: s = [x > 0]; ScaleStore: s = x, where x is the per-element tensor `mask`.  At most one
 // per-element tensor is read (residual or mask), so a unit of 8 outputs costs one optional 16-byte global load,
 // which is fetched one unit ahead of its use.
 
@@ -274,13 +274,16 @@ __device__ __forceinline__ void store_ragged(const GemmParams& p, const float* p
   for (int e = 0; e < count && n + e < p.N; ++e) {
     float v = parked[e] * p.alpha, pre = v;
     if (p.epilogue == (int)Epilogue::MaskStore) v = to_float(mask[(size_t)m * p.ldmask + n + e]) > 0.f ? v : 0.f;
-    else if (p.epilogue == (int)Epilogue::GeluBwdStore) v *= gelu_grad_f(to_float(mask[(size_t)m * p.ldmask + n + e]));
+    else if (p.epilogue == (int)Epilogue::ScaleStore) v *= to_float(mask[(size_t)m * p.ldmask + n + e]);
     else {
       v = v * (cscale ? to_float(cscale[n + e]) : 1.f) + (bias ? to_float(bias[n + e]) : 0.f);
       if (!p.aux_raw) pre = v;
       if (res) v += to_float(res[(size_t)m * p.ldres + n + e]);
       if (p.act == (int)Act::Relu) v = fmaxf(v, 0.f);
-      else if (p.act == (int)Act::Gelu) v = gelu_f(v);
+      else if (p.act == (int)Act::Gelu) {
+        if (p.aux_act_grad) gelu_both_f(v, v, pre);
+        else v = gelu_f(v);
+      }
       if (aux) store_elem(aux + (size_t)m * p.ldaux + n + e, pre);
     }
     store_elem(dst + e, v);
@@ -403,9 +406,9 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
     if (mode == (int)Epilogue::MaskStore) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = x[e] > 0.f ? v[e] : 0.f;
-    } else if (mode == (int)Epilogue::GeluBwdStore) {
+    } else if (mode == (int)Epilogue::ScaleStore) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(x[e]);
+      for (int e = 0; e < 8; ++e) v[e] *= x[e];
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -418,8 +421,13 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
       } else if (p.act == (int)Act::Gelu) {
+        if (p.aux_act_grad) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+          for (int e = 0; e < 8; ++e) gelu_both_f(v[e], v[e], pre[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+        }
       }
       if (aux) *reinterpret_cast<u32x4*>(aux + (size_t)m * p.ldaux + n) = pack_bf16x8(pre);
     }

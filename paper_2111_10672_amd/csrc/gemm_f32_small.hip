@@ -212,7 +212,7 @@ hipError_t launch(const GemmProblem& q, hipStream_t stream) {
 bool gemm_f32_small_accepts(const GemmProblem& p) {
   if (p.dtype != DType::F32 || p.batch != 1 || p.k_splits != 1 || p.alpha != 1.f || p.residual || p.aux_out || p.col_scale) return false;
   if (p.a_gather != Gather::None || p.b_gather != Gather::None) return false;
-  if (p.act == Act::Gelu || p.epilogue == Epilogue::GeluBwdStore) return false;
+  if (p.act == Act::Gelu || p.epilogue == Epilogue::ScaleStore) return false;
   if (p.a_layout == Layout::KRow && p.b_layout == Layout::RowK) return false;
   auto ok = [&](Layout l, int rows, bool pad_zero) { return ((l == Layout::RowK ? p.K : rows) % 4 == 0) || pad_zero; };
   if (!ok(p.a_layout, p.M, p.a_pad_zero) || !ok(p.b_layout, p.N, p.b_pad_zero)) return false;

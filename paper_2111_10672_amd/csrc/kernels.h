@@ -26,7 +26,7 @@ enum class Epilogue : int {
   StoreF32 = 0,      // C float32 = alpha * acc (+ bias[n])
   BiasAct = 1,       // v = alpha * acc * col_scale[n] + bias[n]; aux_out (T) = v if given; C (T) = act(v + residual[m, n])
   MaskStore = 2,     // C (T) = mask[m, n] > 0 ? acc : 0          (ReLU backward fused into the input-gradient product)
-  GeluBwdStore = 3,  // C (T) = acc * gelu'(mask[m, n])           (GELU backward; mask holds the pre-activation)
+  ScaleStore = 3,    // C (T) = acc * mask[m, n]                  (GELU backward; mask holds gelu'(pre-activation) as the forward pass stored it)
 };
 
 enum class Act : int { None = 0, Relu = 1, Gelu = 2 };
@@ -69,6 +69,7 @@ struct GemmProblem {
   void* aux_out = nullptr; int ldaux = 0;          // [M, N], dtype, receives the pre-activation (BiasAct)
   const void* col_scale = nullptr;                 // [N], dtype: v = alpha * acc * col_scale[n] + bias[n]   (BiasAct)
   int aux_raw = 0;                                 // aux_out receives alpha * acc instead of the pre-activation
+  int aux_act_grad = 0;                            // act = Gelu: aux_out receives gelu'(v) instead of v (all the backward pass needs of v)
   int batch = 1;                  // independent products launched together (attention heads)
   BatchStride a_batch, b_batch, c_batch;
   Gather a_gather = Gather::None, b_gather = Gather::None;

@@ -138,6 +138,16 @@ class MlpModel : public Model {
     return SPB_OK;
   }
 
+  void unit_io(int k, int unit, spb_buffer_view* input, spb_buffer_view* output_grad) const override {
+    const int L = num_units;
+    const Plan p = plan(k);
+    // a_unit, the unit's input; unit 0 reads the caller's x
+    *input = unit == 0 ? make_view(SPB_VIEW_CALLER_INPUT, batch_, dims_[0], dims_[0], dtype)
+                       : make_view((long long)p.act[unit], batch_, dims_[unit], ld(unit), dtype);
+    // the input gradient of unit + 1 with the ReLU of this unit fused in: the gradient at this unit's pre-activation
+    *output_grad = (unit == L - 1 || k < 2) ? no_view() : make_view((long long)p.dz[(unit + 1) & 1], batch_, dims_[unit + 1], ld(unit + 1), dtype, 1);
+  }
+
  private:
   int batch_ = 0, per_ = 8;
   std::vector<int64_t> dims_;

@@ -52,6 +52,10 @@ class Model {
   virtual size_t workspace_size(int k) const = 0;
   virtual int forward(const void* x, const int32_t* labels, const int32_t* loss_rows, int k, void* ws, float* loss_out, hipStream_t s) = 0;
   virtual int backward(int k, hipStream_t s) = 0;
+  // Where a forward pass that stashed for depth k keeps the input of unit `unit` (>= L - k), and where the gradient
+  // with respect to that unit's output lies once a backward pass of depth exactly L - unit has run (the unit being
+  // the lowest visited one, nothing has overwritten it).  Host-only.
+  virtual void unit_io(int k, int unit, spb_buffer_view* input, spb_buffer_view* output_grad) const = 0;
 
   int num_units = 0;
   DType dtype = DType::BF16;
@@ -101,6 +105,15 @@ std::unique_ptr<Model> make_encoder(const spb_model_desc& d);
 std::unique_ptr<Model> make_resnet(const spb_model_desc& d);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline spb_buffer_view make_view(long long offset, long long rows, long long cols, long long pitch, DType t, int relu_applied = 0) {
+  spb_buffer_view v;
+  v.offset = offset; v.rows = rows; v.cols = cols; v.pitch = pitch;
+  v.dtype = t == DType::F32 ? SPB_DTYPE_F32 : SPB_DTYPE_BF16; v.relu_applied = relu_applied;
+  return v;
+}
+inline spb_buffer_view no_view() { spb_buffer_view v; v.offset = SPB_VIEW_NONE; v.rows = v.cols = v.pitch = 0; v.dtype = SPB_DTYPE_BF16; v.relu_applied = 0; return v; }
+
 
 }  // namespace spb
 

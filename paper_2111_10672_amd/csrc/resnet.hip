@@ -427,6 +427,30 @@ class ResnetModel : public Model {
     return SPB_OK;
   }
 
+  void unit_io(int k, int unit, spb_buffer_view* input, spb_buffer_view* output_grad) const override {
+    const Plan p = plan(k);
+    const int nb = (int)blocks_.size();
+    // NHWC tensors as [pixels, channels]
+    if (unit == 0) {
+      *input = make_view(SPB_VIEW_CALLER_INPUT, stem_.in_rows(batch_), stem_.cin, stem_.cin, dtype);
+    } else if (unit <= nb) {
+      const Conv& c = blocks_[unit - 1].convs[0];
+      *input = make_view((long long)p.unit[unit - 1].out, c.in_rows(batch_), c.cin, c.cin, dtype);
+    } else {
+      *input = make_view((long long)p.unit[nb].out, (long long)batch_ * final_h_ * final_w_, features_, features_, dtype);
+    }
+    // The gradient entering the top block lies in slot 0 and the slots alternate from block to block.
+    if (unit == nb + 1 || k < 2) {
+      *output_grad = no_view();
+    } else if (unit >= 1) {
+      const Conv& c = blocks_[unit - 1].convs.back();
+      *output_grad = make_view((long long)p.g[(nb - unit) & 1], c.out_rows(batch_), c.cout, c.cout, dtype);
+    } else {
+      const long long rows = pool_ ? (long long)batch_ * pool_h_ * pool_w_ : stem_.out_rows(batch_);
+      *output_grad = make_view((long long)p.g[nb & 1], rows, stem_.cout, stem_.cout, dtype);
+    }
+  }
+
  private:
   int batch_ = 0, classes_ = 0, features_ = 0, final_h_ = 0, final_w_ = 0, pool_h_ = 0, pool_w_ = 0;
   bool pool_ = false;

@@ -4,19 +4,23 @@ Relative error of a gradient tensor is measured against the tensor's own scale, 
 element (an element-wise ratio explodes wherever a ReLU zeroes the reference):
     rel_max = max_i |g_i - ref_i| / max_i |ref_i|        rel_fro = ||g - ref||_F / ||ref||_F
 float32 workloads: both <= 1e-4 against the exact float64 oracle.
-bfloat16 workloads: both <= 2e-2 against the oracle that rounds stored tensors to bfloat16 at the
-same places as the HIP path.  A deep ReLU chain at small batch is not well-conditioned under that
-rounding: a pre-activation that lands on the other side of zero, or of a rounding boundary, switches
-whole terms of a gradient sum, and two correct bfloat16 implementations drift apart layer by layer.
-Where the oracle's own two modes (exact, storage-rounded) differ by more than 2e-2 for a tensor, that
-difference is the tensor's storage-noise floor and replaces 2e-2 as its bound.  A tensor whose
-reference is identically zero must be exactly zero.
+bfloat16 workloads, ONE UNIT AT A TIME (test_parity_per_unit.py: the oracle's unit fed the GPU's own stored
+input and incoming gradient): both <= 2e-2, flat, for every parameter gradient.
+bfloat16 workloads, END TO END: both <= 2e-2 against the oracle that rounds stored tensors to bfloat16 at the
+same places as the HIP path, except where the chain itself is not well-conditioned under that rounding: a
+pre-activation that lands on the other side of zero, or of a rounding boundary, switches whole terms of a
+gradient sum, and two correct bfloat16 implementations drift apart layer by layer.  The distance between the
+oracle's own two modes (exact, storage-rounded) measures that drift per tensor; where it exceeds 2e-2 it
+replaces 2e-2 as the end-to-end bound, but never beyond END_TO_END_CAP.  Every tensor that misses the flat 2e-2
+is printed with its error against both oracle modes.  A tensor whose reference is identically zero must be
+exactly zero.
 """
 from __future__ import annotations
 
 import numpy as np
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+END_TO_END_CAP = 1e-1     # no end-to-end bound is ever looser than this, whatever the oracle's two modes say
 
 
 def rel_max(g, ref):
@@ -29,21 +33,39 @@ def rel_fro(g, ref):
     return float(np.linalg.norm(g - ref) / scale) if scale > 0 else float(np.linalg.norm(g))
 
 
-def check_gradients(gpu: dict, ref: dict, dtype: str, exact: dict | None = None, report=None):
-    """gpu, ref, exact: name -> float64 arrays.  ref is the gated oracle; exact the float64 one (bf16 only)."""
+def end_to_end_bound(dtype: str, mode_distance: float | None) -> float:
+    tol = TOL[dtype]
+    if dtype != "bf16" or mode_distance is None:
+        return tol
+    return min(max(tol, mode_distance), END_TO_END_CAP)
+
+
+def check_gradients(gpu: dict, ref: dict, dtype: str, exact: dict | None = None, report=None, label=""):
+    """gpu, ref, exact: name -> float64 arrays.  ref is the gated oracle; exact the float64 one (bf16 only).
+    Prints every tensor that misses the flat tolerance, with its error against both oracle modes."""
     assert set(gpu) == set(ref), (sorted(gpu), sorted(ref))
     worst = 0.0
+    beyond_flat = []
     for name in ref:
         g, r = np.asarray(gpu[name], dtype=np.float64), ref[name]
         assert g.shape == r.shape, name
         assert np.isfinite(g).all(), f"{name}: non-finite gradient"
         for measure in (rel_max, rel_fro):
-            tol = TOL[dtype]
-            if dtype == "bf16" and exact is not None:
-                tol = max(tol, measure(exact[name], r))
+            distance = measure(exact[name], r) if (dtype == "bf16" and exact is not None) else None
+            tol = end_to_end_bound(dtype, distance)
             err = measure(g, r)
             worst = max(worst, err)
             if report is not None:
                 report.append((name, measure.__name__, err, tol))
+            if err > TOL[dtype]:
+                vs_exact = measure(g, exact[name]) if exact is not None else float("nan")
+                beyond_flat.append(f"    {name} {measure.__name__}: {err:.3e} vs storage-rounded oracle, {vs_exact:.3e} vs exact oracle, "
+                                   f"oracle modes {distance if distance is not None else float('nan'):.3e} apart, bound {tol:.3e}")
             assert err <= tol, f"{name}: {measure.__name__} = {err:.3e} > {tol:.3e}"
+    if beyond_flat:
+        print(f"  {label}: {len(beyond_flat)} measure(s) beyond the flat {TOL[dtype]:.0e} (ill-conditioned under bfloat16 storage):", flush=True)
+        for line in beyond_flat:
+            print(line, flush=True)
+    else:
+        print(f"  {label}: every tensor within the flat {TOL[dtype]:.0e}", flush=True)
     return worst

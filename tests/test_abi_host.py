@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported(repo_root):
     assert set(names) == set(spb.binding.EXPORTS), "binding and header disagree"
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "ragged_mlp_bf16"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "ragged_mlp_bf16", "cfg3", "cfg4", "cfg5", "small_resnet_bottleneck_bf16",
+                                  "mid_resnet_bottleneck_bf16", "small_encoder_bf16", "resnet101_cifar"])
 def test_parameter_list_matches_the_workload(name):
     cfg = wl.get_config(name)
     m = spb.spb_model_create(spb.desc_from_config(cfg))
@@ -120,5 +121,59 @@ def test_worker_depth_rule_and_aggregation_argument_errors():
         with pytest.raises(spb.SpbError) as e:      # parameters not bound
             spb.spb_aggregate_update(m, [1], [none], none, 0.1, 0.9, 0.0, True, 0)
         assert e.value.code == -3
+    finally:
+        spb.spb_model_destroy(m)
+
+
+def test_static_workspace_entry_point_checks_its_arguments_on_the_host():
+    """Everything spb_forward_static refuses, it refuses before any GPU call."""
+    m = spb.spb_model_create(spb.desc_from_config(wl.get_config("cfg2")))
+    big = spb.spb_model_create(spb.desc_from_config(wl.get_config("wide_mlp_bf16")))
+    try:
+        with pytest.raises(spb.SpbError) as e:          # null input
+            spb.spb_forward_static(m, None, 256, None, 1, 256, 0)
+        assert e.value.code == -1
+        with pytest.raises(spb.SpbError) as e:          # depth out of range
+            spb.spb_forward_static(m, 256, 256, None, 9, 256, 0)
+        assert e.value.code == -2
+        with pytest.raises(spb.SpbError) as e:          # nothing bound
+            spb.spb_forward_static(m, 256, 256, None, 1, 256, 0)
+        assert e.value.code == -3
+        assert all(spb.spb_workspace_size(m, k) <= spb.SPB_STATIC_WORKSPACE_BYTES for k in range(9))
+        spb.spb_bind_params(big, [256] * spb.spb_param_count(big))
+        with pytest.raises(spb.SpbError) as e:          # does not fit the fixed array
+            spb.spb_forward_static(big, 256, 256, None, 2, 256, 0)
+        assert e.value.code == -4
+    finally:
+        spb.spb_model_destroy(m)
+        spb.spb_model_destroy(big)
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg5", "small_resnet_bottleneck_bf16"])
+def test_unit_views_lie_inside_the_workspace_and_have_the_units_shapes(name):
+    cfg = wl.get_config(name)
+    m = spb.spb_model_create(spb.desc_from_config(cfg))
+    try:
+        L = spb.spb_num_units(m)
+        total = spb.spb_workspace_size(m, L)
+        size = {"f32": 4, "bf16": 2, "i32": 4}
+        seen = set()
+        for u in range(L):
+            vin, vg = spb.spb_unit_io(m, L, u)
+            assert (vin["offset"] == spb.SPB_VIEW_CALLER_INPUT) == (u == 0)
+            assert (vg["offset"] == spb.SPB_VIEW_NONE) == (u == L - 1)
+            for v in (vin, vg):
+                if v["offset"] >= 0:
+                    assert v["offset"] % 256 == 0 and v["pitch"] >= v["cols"] > 0 and v["rows"] > 0
+                    assert v["offset"] + ((v["rows"] - 1) * v["pitch"] + v["cols"]) * size[v["dtype"]] <= total
+            if vin["offset"] >= 0:
+                assert vin["offset"] not in seen            # every unit's input has a buffer of its own at full depth
+                seen.add(vin["offset"])
+            if u + 1 < L:                                   # what unit u hands up is what unit u + 1 takes in
+                up, _ = spb.spb_unit_io(m, L, u + 1)
+                assert (vg["rows"], vg["cols"]) == (up["rows"], up["cols"])
+        with pytest.raises(spb.SpbError) as e:              # a unit below the cut keeps nothing
+            spb.spb_unit_io(m, 2, L - 3)
+        assert e.value.code == -1
     finally:
         spb.spb_model_destroy(m)

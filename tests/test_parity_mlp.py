@@ -38,7 +38,7 @@ def _compare(cfg, seed, k, perturbed=False):
         assert abs(loss - ref_loss) <= (1e-4 if cfg["dtype"] == "f32" else 5e-3) * abs(ref_loss), (loss, ref_loss)
         gpu = {n: g.double().cpu().numpy() for n, g in model.grad_dict(k).items()}
         report = []
-        check_gradients(gpu, ref, cfg["dtype"], exact, report)
+        check_gradients(gpu, ref, cfg["dtype"], exact, report, label=f"{cfg['name']} seed={seed} k={k}")
         # below the cut: not listed and never written
         listed = set(gpu)
         for info, g in zip(model.infos, model.grads):

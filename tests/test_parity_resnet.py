@@ -41,6 +41,37 @@ def test_small_resnets_every_depth(name, perturbed):
             model.close()
 
 
+def test_mid_size_bottlenecks_element_by_element():
+    """56x56 images at batch 8 through a 64 -> 256 bottleneck stage and a stride-2 128 -> 512 block: 25088 and 6272
+    pixel rows, which take the 128-row and 256-row gathered tiles, the one-tap path at 64 and 128 channels, a
+    stride-2 input gradient and weight gradients cut into many k-slices.  Every entry against the oracle."""
+    name = "mid_resnet_bottleneck_bf16"
+    cfg = wl.get_config(name)
+    params, batch = wl.make_params(cfg, 0, True), wl.make_batch(cfg, 0)
+    n_units = wl.unit_count(cfg)
+    print(f"case {name}: oracle, exact", flush=True)
+    _, exact = oracle.spb_step(cfg, params, batch, n_units)
+    print(f"case {name}: oracle, bfloat16 storage", flush=True)
+    ref_loss, ref = oracle.spb_step(cfg, params, batch, n_units, oracle.round_to_bf16)
+    unit_of = {n: u for n, _s, u, _i in wl.tensor_specs(cfg)}
+    model = spb.SpbModel(cfg, params)
+    try:
+        dev = {n: t.cuda() for n, t in batch.items()}
+        for k in (n_units, 2):
+            print(f"case {name} k={k}", flush=True)
+            for g in model.grads:
+                g.fill_(float("nan"))
+            model.step(dev, k)
+            torch.cuda.synchronize()
+            assert abs(model.loss.item() - ref_loss) <= 5e-3 * abs(ref_loss)
+            gpu = {n: g.double().cpu().numpy() for n, g in model.grad_dict(k).items()}
+            want = {n for n, u in unit_of.items() if u >= n_units - k}
+            assert set(gpu) == want
+            check_gradients(gpu, {n: ref[n] for n in want}, "bf16", {n: exact[n] for n in want}, label=f"{name} k={k}")
+    finally:
+        model.close()
+
+
 def test_resnet_workspace_grows_with_depth():
     cfg = wl.get_config("small_resnet_bottleneck_bf16")
     m = spb.spb_model_create(spb.desc_from_config(cfg))

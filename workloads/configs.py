@@ -86,6 +86,13 @@ CONFIGS = {
     "small_resnet_bottleneck_bf16": dict(family="resnet_bottleneck", dtype="bf16", batch=2, image=[20, 20, 3],
                                          stem=dict(kernel=7, stride=2, pad=3, pool=True, width=16),
                                          stage_blocks=[2, 1], stage_widths=[32, 64], classes=11, depths=[0, 1, 2, 3, 4, 5]),
+    # one bottleneck stage 64 -> 256 on 56x56 images and a stride-2 block 128 -> 512 behind it, batch 8: products of
+    # 25088 x 64..256 and 6272 x 128..512 rows, which take the 128-row and 256-row gathered tiles, the one-tap path
+    # at 64 and 128 channels, a stride-2 input gradient and weight gradients cut into 64 and more k-slices; small
+    # enough for the oracle to check every entry
+    "mid_resnet_bottleneck_bf16": dict(family="resnet_bottleneck", dtype="bf16", batch=8, image=[56, 56, 3],
+                                       stem=dict(kernel=3, stride=1, pad=1, pool=False, width=64),
+                                       stage_blocks=[2, 1], stage_widths=[256, 512], classes=10, depths=[1, 2, 3, 4, 5]),
     # the 35-unit stack of resnet101_cifar at toy widths
     "small_resnet101_bf16": dict(family="resnet_bottleneck", dtype="bf16", batch=2, image=[8, 8, 3],
                                  stem=dict(kernel=3, stride=1, pad=1, pool=False, width=16),
