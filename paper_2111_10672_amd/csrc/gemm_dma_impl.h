@@ -130,8 +130,10 @@ struct TileSource {
     }
   }
 
-  // Issue tile t (tiles must be issued in increasing order, one after the other).
-  __device__ __forceinline__ void issue(int t, int K, char* tile, int wave, int ld, const ConvGeom& cg) {
+  // Issue tile t (tiles must be issued in increasing order, one after the other).  PARTS > 1: only the
+  // instructions i with i % PARTS == part, and the parts of a tile in increasing order.
+  template <int PARTS = 1>
+  __device__ __forceinline__ void issue(int t, int K, char* tile, int wave, int ld, const ConvGeom& cg, int part = 0) {
     if constexpr (G == Gather::ConvRows) {
       if (one_tap) {
         const int r = (u_tap * (65536 / cg.s + 1)) >> 16, c = u_tap - r * cg.s;   // tap = r * S + c, exact for tap < 256
@@ -140,17 +142,21 @@ struct TileSource {
         const bool tap_ok = u_tap < cg.r * cg.s;
 #pragma unroll
         for (int i = 0; i < kInstr; ++i) {
+          if (PARTS > 1 && i % PARTS != part) continue;
           const bool ok = tap_ok && in_rows[i] && (unsigned)(g1[i] + dr) < (unsigned)cg.sh && (unsigned)(g2[i] + dc) < (unsigned)cg.sw;
           const char* src = ok ? ptr[i] + tap_bytes : reinterpret_cast<const char*>(kZeroChunk);
           __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, 0, 0);
         }
-        u_chan += kTileK;
-        if (u_chan >= cg.sc) { u_chan = 0; ++u_tap; }
+        if (part == PARTS - 1) {   // the tile is complete: on to the next tap or channel block
+          u_chan += kTileK;
+          if (u_chan >= cg.sc) { u_chan = 0; ++u_tap; }
+        }
         return;
       }
     }
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) {
+      if (PARTS > 1 && i % PARTS != part) continue;
       const char* src = reinterpret_cast<const char*>(kZeroChunk);
       if constexpr (G == Gather::None) {
         if (in_rows[i] && t * kTileK + k_in_tile[i] < K) src = ptr[i];
@@ -228,6 +234,21 @@ __device__ __forceinline__ void fragments_ready(u32x4 (&a)[NA], u32x4 (&b)[NB]) 
   for (int i = 0; i < NA; ++i) asm volatile("" : "+v"(a[i]));
 #pragma unroll
   for (int j = 0; j < NB; ++j) asm volatile("" : "+v"(b[j]));
+}
+
+// The same fetch with every LDS read written as assembly, for the loop that keeps direct-to-LDS loads in flight
+// across its LDS reads on purpose: nothing here lets the compiler tie a read to those loads and wait for them,
+// and the reads stay in source order.  Valid after an s_waitcnt lgkmcnt and a pin (fragments_ready, pin_fragment).
+__device__ __forceinline__ u32x4 lds_read_b128_asm(const char* addr) {
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)addr;
+  u32x4 w;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(w) : "v"(lds_addr));
+  return w;
+}
+template <int ROWS, Layout L>
+__device__ __forceinline__ u32x4 read_fragment_asm(const char* tile, int frag_row0, int kg, int lane) {
+  if constexpr (L == Layout::RowK) return lds_read_b128_asm(tile + lds_offset(frag_row0 + (lane & 31), 2 * kg + (lane >> 5)));
+  else return read_fragment<ROWS, L>(tile, frag_row0, kg, lane);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return bf16_pack2(lo, hi); }
@@ -601,6 +622,214 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
   store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z));
 }
 
+// The same product with the tile loop written as a software pipeline.  In the kernel above a wave does one thing
+// at a time (issue a tile's loads, read LDS, multiply) and a workgroup's waves do it together, so the vector-memory
+// path, the LDS and the matrix cores of a CU take turns.  Here every k-group (16 of k) is a block of MFMAs on the
+// fragments fetched during the block before, and between those MFMAs the wave issues the LDS reads of the next
+// k-group's fragments and its share of a later tile's direct-to-LDS loads, one instruction at a time: the three
+// pipes run side by side, and the loads of a tile are spread over several blocks instead of arriving at the
+// memory path in one burst.  One barrier per tile, in front of the tile's last k-group: by then a wave has all of
+// the tile in registers (so the buffer may be overwritten: tile t + STAGES goes there, its parts issued in the
+// blocks that follow) and knows its own loads of tile t + 1 have landed (so everybody may read it: the last block
+// fetches tile t + 1's first fragments).
+//   STAGES = 3: a tile's loads in 4 parts; they have a whole tile's time to land.
+//   STAGES = 2 (tiles too large for three): 2 parts, in the block after the barrier and the one after that, which
+//   leaves them two blocks to land.
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, int KGB, Layout LA, Layout LB, Gather GA, Gather GB>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(GemmParams p) {
+  constexpr int NW = WAVES_M * WAVES_N;
+  static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
+  static_assert(STAGES == 2 || STAGES == 3, "ring depth");
+  static_assert(KGB == 1 || KGB == 2, "k-groups per block");
+  constexpr int NB = 4 / KGB;                          // blocks per tile
+  constexpr int PARTS = STAGES == 3 ? NB : NB / 2;     // a tile's loads: in every block, or in the two after the barrier
+  static_assert(PARTS >= 1, "a ring of two stages needs four blocks per tile");
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  static_assert(TM >= 1 && TN >= 1 && WM % 32 == 0 && WN % 32 == 0, "wave tile is a multiple of 32x32");
+  constexpr int kMfma = KGB * TM * TN, kReads = KGB * (TM + TN);   // per block
+  constexpr int kReadsPerSlot = (kReads + kMfma - 1) / kMfma;
+  constexpr int kStageBytes = (BM + BN) * kRowBytes;
+  static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
+  using SourceA = TileSource<BM, LA, GA, NW>;
+  using SourceB = TileSource<BN, LB, GB, NW>;
+  constexpr int kLoadsPerTile = SourceA::kInstr + SourceB::kInstr;
+  static_assert(kLoadsPerTile < 64, "vmcnt range");
+
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  int tile_m, tile_n;
+  xcd_tile_grouped(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+
+  SourceA src_a;
+  SourceB src_b;
+  const int z = blockIdx.y;  // batch entry, or slice of the k range
+  int t_first = 0, n_steps = (p.K + kTileK - 1) / kTileK;
+  if (p.k_tiles_per_split > 0) {
+    t_first = z * p.k_tiles_per_split;
+    n_steps = min(n_steps, t_first + p.k_tiles_per_split);
+  }
+  const int n = max(n_steps - t_first, 0);          // tiles of this workgroup, numbered from 0 below
+  src_a.init(static_cast<const bf16_t*>(p.A) + batch_offset_z(p.a_batch, z), p.lda, m0, p.M, wave, lane, t_first, p.conv);
+  src_b.init(static_cast<const bf16_t*>(p.B) + batch_offset_z(p.b_batch, z), p.ldb, n0, p.N, wave, lane, t_first, p.conv);
+  auto stage_of = [&](int t) { return lds + (t % STAGES) * kStageBytes; };
+  auto issue_part = [&](int t, int part) {           // tiles in increasing order, a tile's parts in increasing order
+    if (t >= n) return;
+    char* stage = stage_of(t);
+    src_a.template issue<PARTS>(t_first + t, p.K, stage, wave, p.lda, p.conv, part);
+    src_b.template issue<PARTS>(t_first + t, p.K, stage + BM * kRowBytes, wave, p.ldb, p.conv, part);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // bias gradient of a weight-gradient product (see the kernel above): the k-rows are fetched in a tile's first
+  // block and added in its second
+  constexpr int kChunks = BM / 8, kPhases = 64 * NW / kChunks, kSumReads = kTileK / kPhases;
+  static_assert(kPhases >= 1 && kTileK % kPhases == 0 && (size_t)kPhases * BM * 4 <= (size_t)STAGES * kStageBytes, "row-sum partition");
+  const bool want_row_sum = LA == Layout::KRow && p.a_row_sum != nullptr && tile_n == 0;
+  float row_sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int sum_chunk = threadIdx.x % kChunks, sum_phase = threadIdx.x / kChunks;
+  u32x4 sum_rows[kSumReads];
+
+  auto pin = [] { __builtin_amdgcn_sched_barrier(0); };   // the instruction scheduler moves nothing across this point
+  auto lds_done = [] { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); };
+
+  // Two sets of fragment registers: a block multiplies one while the reads of the next block fill the other.
+  // Within a set: the A fragments of the block's k-groups, then the B fragments.
+  u32x4 fa[2][KGB * TM], fb[2][KGB * TN];
+  auto keep = [&](int b) {
+#pragma unroll
+    for (int i = 0; i < KGB * TM; ++i) asm volatile("" : "+v"(fa[b][i]));
+#pragma unroll
+    for (int j = 0; j < KGB * TN; ++j) asm volatile("" : "+v"(fb[b][j]));
+  };
+  // read number r (0 .. kReads-1) of the block that starts at k-group kg0 of the tile at (as, bs), into set b
+  auto fetch = [&](int b, const char* as, const char* bs, int kg0, int r) {
+    if (r < KGB * TM) fa[b][r] = read_fragment_asm<BM, LA>(as, wm * WM + (r % TM) * 32, kg0 + r / TM, lane);
+    else if (r < kReads) fb[b][r - KGB * TM] = read_fragment_asm<BN, LB>(bs, wn * WN + ((r - KGB * TM) % TN) * 32, kg0 + (r - KGB * TM) / TN, lane);
+  };
+
+  // ---- prologue: tiles 0 .. STAGES-2 whole, the first part of tile STAGES-1, then tile 0's first fragments
+#pragma unroll
+  for (int t = 0; t < STAGES - 1; ++t)
+#pragma unroll
+    for (int part = 0; part < PARTS; ++part) issue_part(t, part);
+  issue_part(STAGES - 1, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  pin();
+  __builtin_amdgcn_s_barrier();
+  pin();
+  if (n > 0) {
+    const char* as = stage_of(0);
+#pragma unroll
+    for (int r = 0; r < kReads; ++r) fetch(0, as, as + BM * kRowBytes, 0, r);
+  }
+
+  for (int t = 0; t < n; ++t) {
+    const char* as = stage_of(t);
+    const char* bs = as + BM * kRowBytes;
+    const char* as_next = stage_of(t + 1);
+    const char* bs_next = as_next + BM * kRowBytes;
+    const bool more = t + 1 < n;
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk) {
+      const int cur = blk & 1, nxt = cur ^ 1;
+      const bool last = blk == NB - 1;
+      // ---- the fragments of this block are in registers
+      lds_done();
+      keep(cur);
+      if constexpr (LA == Layout::KRow) {
+        if (blk == 1 && want_row_sum) {
+#pragma unroll
+          for (int r = 0; r < kSumReads; ++r) {
+            asm volatile("" : "+v"(sum_rows[r]));
+            float f[8];
+            unpack_bf16x8(sum_rows[r], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) row_sum[e] += f[e];
+          }
+        }
+      }
+      if (last) {
+        // All of tile t is in registers; this wave's loads of tile t + 1 have landed (tile t + 2, when the ring
+        // has three stages, may stay in flight).
+        if (STAGES == 3 && t + 2 < n) __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoadsPerTile, 15));
+        else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
+        pin();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      pin();
+      // ---- MFMAs of this block; between them the next block's fragment reads and one part of a later tile's loads
+      const char* ra = last ? as_next : as;
+      const char* rb = last ? bs_next : bs;
+      const int kg_next = last ? 0 : (blk + 1) * KGB;
+      const bool fetching = !last || more;
+      const int load_tile = last ? t + STAGES : t + STAGES - 1;   // part 0 right after the barrier, the others in the next tile's blocks
+      const int load_part = last ? 0 : blk + 1;
+#pragma unroll
+      for (int g = 0; g < KGB; ++g) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int idx = (g * TM + i) * TN + j;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[cur][g * TM + i]),
+                                                                __builtin_bit_cast(bf16x8, fb[cur][g * TN + j]), acc[i][j], 0, 0, 0);
+            if (fetching) {
+#pragma unroll
+              for (int r = idx * kReadsPerSlot; r < (idx + 1) * kReadsPerSlot; ++r) fetch(nxt, ra, rb, kg_next, r);
+            }
+            if (idx == 0 && load_part < PARTS) issue_part(load_tile, load_part);
+            pin();
+          }
+        }
+      }
+      if constexpr (LA == Layout::KRow) {
+        if (blk == 0 && want_row_sum) {
+#pragma unroll
+          for (int r = 0; r < kSumReads; ++r) {
+            const int k = sum_phase + r * kPhases;
+            const int pc = (sum_chunk + krow_rot<BM>(k)) % kChunks;
+            sum_rows[r] = lds_read_b128_asm(as + k * (BM * 2) + pc * 16);
+          }
+          pin();
+        }
+      }
+    }
+  }
+  lds_done();
+  // Every wave is past the last tile's barrier, which it reached with the whole tile in registers: the ring is dead.
+  __syncthreads();
+  if constexpr (LA == Layout::KRow) {
+    if (want_row_sum) {  // uniform over the workgroup
+      float* part = reinterpret_cast<float*>(lds);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part[sum_phase * BM + sum_chunk * 8 + e] = row_sum[e];
+      __syncthreads();
+      if (threadIdx.x < BM) {
+        float v = 0.f;
+#pragma unroll
+        for (int ph = 0; ph < kPhases; ++ph) v += part[ph * BM + threadIdx.x];
+        if (m0 + (int)threadIdx.x < p.M) p.a_row_sum[m0 + threadIdx.x] = v;
+      }
+      __syncthreads();
+    }
+  }
+  float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (WN + 4));
+  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z));
+}
+
 // Small products (at most a few workgroups per CU) are a chain of latencies, not a throughput problem, and the
 // one throughput that does bound them is a CU's vector-memory path of about 57 bytes per clock.  So: tiles small
 // enough that every CU gets one (32 x 32 or 64 x 64), and no barrier in the tile loop at all: each of the four
@@ -815,6 +1044,25 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
   return hipGetLastError();
 }
 
+template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, int KGB, Layout LA, Layout LB, Gather GA, Gather GB>
+hipError_t launch_tile_pipe(const GemmProblem& q, hipStream_t stream) {
+  GemmParams p = make_params(q, BM, BN);
+  int grid_y = q.batch;
+  if (q.k_splits > 1) {
+    const int tiles = (q.K + kTileK - 1) / kTileK;
+    p.k_tiles_per_split = (tiles + q.k_splits - 1) / q.k_splits;
+    p.c_batch.outer = (long long)q.M * q.ldc; p.c_batch.inner = 0; p.c_batch.inner_count = 1;
+    grid_y = q.k_splits;
+  }
+  constexpr size_t lds_bytes = (size_t)STAGES * (BM + BN) * kRowBytes;
+  static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
+  auto kernel = gemm_bf16_pipe_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, KGB, LA, LB, GA, GB>;
+  if (lds_bytes > 64 * 1024)
+    if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes); e != hipSuccess) return e;
+  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  return hipGetLastError();
+}
+
 // Tile choice.  A 256 x 256 tile reads half as many operand bytes per flop from L2 as a 128 x 128 one, which is
 // what large products need.  A
 // dimension of 64 or less (a 64-channel convolution) gets a 64-wide tile so that no matrix-core work is spent
@@ -848,7 +1096,7 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   const long t256 = tiles(256, 256);
   // (a k range of one or two tiles has nothing to reuse: such products are bound by memory and run better as two
   // 128 x 128 workgroups per CU)
-  if (q.M >= 256 && q.N >= 256 && q.K > 128 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile<256, 256, 2, 2, 4, LA, LB, GA, GB>(q, stream);
+  if (q.M >= 256 && q.N >= 256 && q.K > 128 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile_pipe<256, 256, 2, 2, 4, 1, LA, LB, GA, GB>(q, stream);
   // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
   // alone on its CU needs a third stage in flight instead.
   if (tiles(128, 128) > 256) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
@@ -856,7 +1104,7 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
     // one round of lone workgroups: convolutions (gathered operands) did 2-5 % better as two 128 x 64 workgroups per
     // CU; plain products were level, and 128 x 128 leaves LDS for a weight-gradient workgroup of the second stream
     if constexpr (GA != Gather::None || GB != Gather::None) return launch_tile<128, 64, 3, 4, 1, LA, LB, GA, GB>(q, stream);
-    else return launch_tile<128, 128, 3, 2, 2, LA, LB, GA, GB>(q, stream);
+    else return launch_tile_pipe<128, 128, 3, 2, 4, 2, LA, LB, GA, GB>(q, stream);   // eight waves: a lone workgroup needs two per SIMD to hide its own latencies
   }
   // 64 x 64: the ring depth that lets every tile be resident at once (two or three workgroups per CU).
   if (tiles(64, 64) > 512) return launch_tile<64, 64, 3, 2, 2, LA, LB, GA, GB>(q, stream);
