@@ -385,10 +385,17 @@ def main():
         n = args.calibrate_copy << 20
         src = torch.ones(n // 4, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        e0.record()
         for _ in range(10):
             torch.add(src, 0.0, out=dst)      # one read and one write of n bytes per launch
+        e1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 10}))
+        us = e0.elapsed_time(e1) * 1e3 / 10
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 11, "us_per_launch": round(us, 2),
+                          "gbps": round(2 * n / us / 1e3, 1), "frac_hbm_peak": round(2 * n / us / 1e3 / PEAK["hbm"], 4)}))
         return
 
     if args.table1:

@@ -66,20 +66,28 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
       *reinterpret_cast<u32x4*>(dy + off) = pack8(o);
       if (dsum) *reinterpret_cast<u32x4*>(dsum + off) = pack8(d);
     };
+    // The three inputs are read here for the last time in the step (the gradient, the kept pre-affine output, the
+    // kept activation): streaming loads, so they do not push the freshly written dy, which the next product reads,
+    // out of the caches.  Four rows per trip, all their loads requested before the first is used.
     const u32x4 zero = {0u, 0u, 0u, 0u};
+    auto fetch = [&](const uint16_t* base, size_t off) { return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off)); };
     long long r = first + lane_row;
-    for (; r + rows_per_pass < last; r += 2 * rows_per_pass) {
-      const size_t off0 = (size_t)r * channels + chunk * 8, off1 = off0 + (size_t)rows_per_pass * channels;
-      const u32x4 d0 = *reinterpret_cast<const u32x4*>(dout + off0), d1 = *reinterpret_cast<const u32x4*>(dout + off1);
-      const u32x4 y0 = *reinterpret_cast<const u32x4*>(y + off0), y1 = *reinterpret_cast<const u32x4*>(y + off1);
-      const u32x4 a0 = act ? *reinterpret_cast<const u32x4*>(act + off0) : zero, a1 = act ? *reinterpret_cast<const u32x4*>(act + off1) : zero;
-      finish(off0, d0, y0, a0);
-      finish(off1, d1, y1, a1);
+    const size_t pass = (size_t)rows_per_pass * channels;
+    for (; r + 3 * rows_per_pass < last; r += 4 * rows_per_pass) {
+      const size_t off0 = (size_t)r * channels + chunk * 8;
+      u32x4 d[4], yv[4], a[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        d[u] = fetch(dout, off0 + u * pass);
+        yv[u] = fetch(y, off0 + u * pass);
+        a[u] = act ? fetch(act, off0 + u * pass) : zero;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) finish(off0 + u * pass, d[u], yv[u], a[u]);
     }
-    if (r < last) {
+    for (; r < last; r += rows_per_pass) {
       const size_t off = (size_t)r * channels + chunk * 8;
-      finish(off, *reinterpret_cast<const u32x4*>(dout + off), *reinterpret_cast<const u32x4*>(y + off),
-             act ? *reinterpret_cast<const u32x4*>(act + off) : zero);
+      finish(off, fetch(dout, off), fetch(y, off), act ? fetch(act, off) : zero);
     }
   }
   if (lane_row < rows_per_pass) {  // lanes past the tensor's last chunk park zeros

@@ -1,5 +1,7 @@
 // Pieces shared by the GEMM kernels: vector types, bfloat16 storage helpers, kernel parameters, epilogue.
 #pragma once
+#include <utility>
+
 #include "kernels.h"
 
 namespace spb {
@@ -12,6 +14,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct bf16_t { uint16_t bits; };
 
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose index is a constant expression
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
+
 constexpr int kThreads = 256;
 constexpr int kRowBytes = 128;  // bytes of k per LDS row and per tile step
 constexpr int kChunks = 8;      // 16-byte chunks per LDS row
@@ -20,8 +28,12 @@ template <typename T> struct Elem;
 template <> struct Elem<float> { static constexpr int kPerChunk = 4; static constexpr int kTileK = 32; };
 template <> struct Elem<bf16_t> { static constexpr int kPerChunk = 8; static constexpr int kTileK = 64; };
 
+// Where 16-byte chunk `chunk` (8 bf16 of k) of row `row` of a RowK tile lies: rows of 128 bytes whose chunks are
+// permuted by the row's low five bits, so that the 32 rows one matrix-core operand read touches fall into different
+// banks.  Only the position of the row inside its 32-row fragment enters, which makes a fragment's address the
+// address of fragment 0 plus a constant.
 __device__ __forceinline__ int lds_offset(int row, int chunk) {
-  return row * kRowBytes + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
+  return row * kRowBytes + (((chunk ^ row ^ ((row >> 3) & 3)) & 7) << 4);
 }
 
 __device__ __forceinline__ float to_float(float v) { return v; }

@@ -46,29 +46,41 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
 
 // Rotation (in 16-byte chunks) of k-row k of a KRow tile, so that the four k-rows one transposing read
 // touches fall into different 64-byte bank groups.
+// A k-row is ROWS * 2 bytes, so where consecutive k-rows start (mod the 256 bytes of the banks) depends on ROWS:
+// a multiple of 256 bytes (ROWS = 128, 256): every k-row starts in the same place and k-row k is rotated by k % 4
+// groups; an odd multiple of 128 bytes (ROWS = 64, 192): k-rows already alternate between the two halves, and the
+// rotation only has to separate k from k + 2.  (With ROWS = 192 the first rule sends k and k + 2 to the same
+// banks wherever the rotation wraps around the row.)
 template <int ROWS>
 __device__ __forceinline__ int krow_rot(int k) {
-  if constexpr (ROWS >= 128) return (k & 3) << 2;
-  else if constexpr (ROWS == 64) return ((k >> 1) & 1) << 2;
+  if constexpr ((ROWS * 2) % 256 == 0) return (k & 3) << 2;
+  else if constexpr ((ROWS * 2) % 256 == 128) return ((k >> 1) & 1) << 2;
   else return 0;
 }
 
 // Where one lane's 16-byte chunks of an operand tile come from.  Everything that does not change from
 // tile to tile is worked out once; tiles are issued in increasing order, so what does change (the tap and
 // channel a chunk's k falls on, the pixel a k-row stands for) is stepped, never divided out again.
-// Every wave issues exactly kInstr direct-to-LDS instructions per tile, whatever its lanes' predicates:
-// a lane outside the matrix (or in a convolution's zero padding) fetches a chunk of zeros instead, so the
-// vmcnt arithmetic of the tile loop holds and rows or k beyond the matrix multiply as zero.
+// Every wave issues exactly kInstr direct-to-LDS instructions per tile, whatever its lanes' predicates, so
+// the vmcnt arithmetic of the tile loop holds: a lane whose k lies beyond K (or, gathered operands, whose pixel
+// lies in the zero padding or beyond the tensor) fetches a chunk of zeros instead.
 template <int ROWS, Layout L, Gather G, int NW>
 struct TileSource {
   static constexpr int kInstr = ROWS / (8 * NW);
   static_assert(ROWS % (8 * NW) == 0 && kInstr >= 1, "tile rows must fill whole wave instructions");
   static_assert(G == Gather::None || (G == Gather::ConvRows) == (L == Layout::RowK), "gather kind fixes the LDS layout");
-  const char* ptr[kInstr];  // Plain: this lane's chunk in tile 0.  Gathers: the tensor's base.
+  const char* ptr[kInstr];  // Gathers: the tensor's base (or, one tap per tile, this lane's pixel at tap (0, 0)).
   int k_in_tile[kInstr];    // k of the chunk's first element relative to the tile start
   bool in_rows[kInstr];
   int row_idx[kInstr];      // first row (of the operand) this lane's chunk covers
   size_t tile_step;         // Plain: bytes from one tile to the next
+  // Plain operands: a chunk's address is a wave-uniform panel address, stepped from tile to tile with scalar
+  // arithmetic, plus a 32-bit lane offset that never changes.  Rows beyond the matrix are not redirected to zeros:
+  // their offset is clamped onto the last rows of the matrix, whose values then fill result rows (or columns) that
+  // no epilogue stores.  Only k beyond K must multiply as zero, and only the last tile can contain such k.
+  const char* panel;        // tile t_first of this workgroup's rows
+  uint32_t voff[kInstr];
+  int t_first;
   // gather state, per instruction
   int tap[kInstr], chan[kInstr];           // ConvRows, ConvWeightT: where this lane's k of the next tile falls; ConvPatchT: fixed (tap, ci) of its rows
   int g0[kInstr], g1[kInstr], g2[kInstr];  // ConvRows: pixel base, row term, column term.  ConvPatchT: image, pixel in image of the next tile's k-row.
@@ -95,7 +107,7 @@ struct TileSource {
       if constexpr (L == Layout::RowK) {
         const int row = slot >> 3, pc = slot & 7;
         gr = row0 + row;
-        k = ((pc ^ row ^ (row >> 3)) & 7) << 3;
+        k = ((pc ^ row ^ ((row >> 3) & 3)) & 7) << 3;   // the inverse of lds_offset
       } else {
         constexpr int kRowChunks = ROWS / 8;
         k = slot / kRowChunks;
@@ -106,7 +118,14 @@ struct TileSource {
       in_rows[i] = gr < nrows;
       row_idx[i] = gr;
       if constexpr (G == Gather::None) {
-        ptr[i] = reinterpret_cast<const char*>(L == Layout::RowK ? base + (size_t)gr * ld + k : base + (size_t)k * ld + gr) + (size_t)t0 * tile_step;
+        t_first = t0;
+        if constexpr (L == Layout::RowK) {
+          panel = reinterpret_cast<const char*>(base + (size_t)row0 * ld) + (size_t)t0 * tile_step;
+          voff[i] = (uint32_t)(min(gr, nrows - 1) - row0) * (uint32_t)ld * 2u + (uint32_t)k * 2u;
+        } else {
+          panel = reinterpret_cast<const char*>(base) + (size_t)t0 * tile_step;
+          voff[i] = (uint32_t)k * (uint32_t)ld * 2u + (uint32_t)(gr < nrows ? gr : ((nrows - 1) & ~7)) * 2u;   // a chunk is 8 rows
+        }
       } else {
         ptr[i] = reinterpret_cast<const char*>(base);
         const int k_abs = t0 * kTileK + k;
@@ -154,13 +173,34 @@ struct TileSource {
         return;
       }
     }
+    if constexpr (G == Gather::None) {
+      const char* pt = panel + (size_t)(t - t_first) * tile_step;      // uniform over the wave
+      if ((t + 1) * kTileK <= K) {                                     // a whole tile: no lane has anything to check
+        // Written as assembly to get the scalar-base form (address = SGPR pair + 32-bit lane offset): through the
+        // builtin the compiler keeps a 64-bit pointer per instruction in VGPRs, steps each with vector adds and
+        // folds this branch into per-lane selects, a dozen vector instructions per load that compete with the
+        // MFMAs for issue.  M0 holds the LDS address of the KiB the wave's 64 chunks fill.
+#pragma unroll
+        for (int i = 0; i < kInstr; ++i) {
+          if (PARTS > 1 && i % PARTS != part) continue;
+          const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)(tile + (i * NW + wave) * 1024);
+          asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(voff[i]), "s"(pt), "s"(dst) : "m0");
+        }
+      } else {                                                         // the last tile of a k range that ends inside it
+#pragma unroll
+        for (int i = 0; i < kInstr; ++i) {
+          if (PARTS > 1 && i % PARTS != part) continue;
+          const char* src = t * kTileK + k_in_tile[i] < K ? pt + voff[i] : reinterpret_cast<const char*>(kZeroChunk);
+          __builtin_amdgcn_global_load_lds((global_ptr_t)src, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, 0, 0);
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < kInstr; ++i) {
       if (PARTS > 1 && i % PARTS != part) continue;
       const char* src = reinterpret_cast<const char*>(kZeroChunk);
       if constexpr (G == Gather::None) {
-        if (in_rows[i] && t * kTileK + k_in_tile[i] < K) src = ptr[i];
-        ptr[i] += tile_step;
       } else if constexpr (G == Gather::ConvRows) {
         const int taps = cg.r * cg.s;
         const int r = (tap[i] * (65536 / cg.s + 1)) >> 16, c = tap[i] - r * cg.s;   // tap = r * S + c, exact for tap < 256
@@ -250,6 +290,52 @@ __device__ __forceinline__ u32x4 read_fragment_asm(const char* tile, int frag_ro
   if constexpr (L == Layout::RowK) return lds_read_b128_asm(tile + lds_offset(frag_row0 + (lane & 31), 2 * kg + (lane >> 5)));
   else return read_fragment<ROWS, L>(tile, frag_row0, kg, lane);
 }
+
+// MFMA operand reads with every lane-dependent part of the address worked out once.  For a RowK tile the lane part
+// depends on the k-group (the chunk permutation is an XOR) but not on the fragment: 4 offsets, fragment i adds
+// i * 32 rows as an instruction offset.  For a KRow tile it depends on the fragment (where the rotation wraps
+// around the row) but not on the k-group: T offsets, k-group kg and half h add (16 kg + 4 h) k-rows as an
+// instruction offset.  at(tile) adds a tile's LDS address to them: one vector add each per tile instead of
+// one or two per read.
+template <int ROWS, Layout L, int T>
+struct FragmentReader {
+  static constexpr int kN = L == Layout::RowK ? 4 : T;
+  uint32_t off[kN];
+  __device__ __forceinline__ void init(int wave_row0, int lane) {   // wave_row0: a multiple of 32
+    if constexpr (L == Layout::RowK) {
+#pragma unroll
+      for (int kg = 0; kg < 4; ++kg) off[kg] = (uint32_t)lds_offset(wave_row0 + (lane & 31), 2 * kg + (lane >> 5));
+    } else {
+      constexpr int kRowChunks = ROWS / 8;
+      const int j = lane & 15, g = lane >> 4;
+#pragma unroll
+      for (int i = 0; i < T; ++i) {
+        const int row = wave_row0 + 32 * i + 16 * (g & 1) + 4 * (j & 3);
+        const int k = 8 * (g >> 1) + (j >> 2);                    // 16 kg + 4 h is a multiple of 4: it leaves the rotation alone
+        const int pc = ((row >> 3) + krow_rot<ROWS>(k)) % kRowChunks;
+        off[i] = (uint32_t)(k * (ROWS * 2) + pc * 16 + (row & 7) * 2);
+      }
+    }
+  }
+  __device__ __forceinline__ void at(uint32_t tile_lds_address, uint32_t (&out)[kN]) const {
+#pragma unroll
+    for (int n = 0; n < kN; ++n) out[n] = off[n] + tile_lds_address;
+  }
+  // fragment I, k-group KG of the tile whose addresses are `a`; valid after an s_waitcnt lgkmcnt and a pin
+  template <int I, int KG>
+  static __device__ __forceinline__ u32x4 read(const uint32_t (&a)[kN]) {
+    u32x4 out;
+    if constexpr (L == Layout::RowK) {
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(out) : "v"(a[KG]), "n"(I * 32 * kRowBytes));
+    } else {
+      uint2 lo, hi;
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(a[I]), "n"((16 * KG) * (ROWS * 2)));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(a[I]), "n"((16 * KG + 4) * (ROWS * 2)));
+      out[0] = lo.x; out[1] = lo.y; out[2] = hi.x; out[3] = hi.y;
+    }
+    return out;
+  }
+};
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return bf16_pack2(lo, hi); }
 
@@ -712,10 +798,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
 #pragma unroll
     for (int j = 0; j < KGB * TN; ++j) asm volatile("" : "+v"(fb[b][j]));
   };
-  // read number r (0 .. kReads-1) of the block that starts at k-group kg0 of the tile at (as, bs), into set b
-  auto fetch = [&](int b, const char* as, const char* bs, int kg0, int r) {
-    if (r < KGB * TM) fa[b][r] = read_fragment_asm<BM, LA>(as, wm * WM + (r % TM) * 32, kg0 + r / TM, lane);
-    else if (r < kReads) fb[b][r - KGB * TM] = read_fragment_asm<BN, LB>(bs, wn * WN + ((r - KGB * TM) % TN) * 32, kg0 + (r - KGB * TM) / TN, lane);
+  using ReaderA = FragmentReader<BM, LA, TM>;
+  using ReaderB = FragmentReader<BN, LB, TN>;
+  ReaderA reader_a;
+  ReaderB reader_b;
+  reader_a.init(wm * WM, lane);
+  reader_b.init(wn * WN, lane);
+  uint32_t at_a[ReaderA::kN], at_b[ReaderB::kN];       // the tile being multiplied
+  uint32_t next_a[ReaderA::kN], next_b[ReaderB::kN];   // the tile after it (its first block is fetched during this tile's last)
+  auto lds_address = [&](int t) { return (uint32_t)(uintptr_t)(lds_ptr_t)stage_of(t); };
+  // read number R (0 .. kReads-1) of the block that starts at k-group KG0, from the tile at (a, b), into set `set`
+  auto fetch = [&](auto set, auto kg0, auto r, const uint32_t (&a)[ReaderA::kN], const uint32_t (&b)[ReaderB::kN]) {
+    constexpr int S = decltype(set)::value, KG0 = decltype(kg0)::value, R = decltype(r)::value;
+    if constexpr (R < KGB * TM) fa[S][R] = ReaderA::template read<R % TM, KG0 + R / TM>(a);
+    else if constexpr (R < kReads) fb[S][R - KGB * TM] = ReaderB::template read<(R - KGB * TM) % TN, KG0 + (R - KGB * TM) / TN>(b);
   };
 
   // ---- prologue: tiles 0 .. STAGES-2 whole, the first part of tile STAGES-1, then tile 0's first fragments
@@ -729,21 +825,20 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
   __builtin_amdgcn_s_barrier();
   pin();
   if (n > 0) {
-    const char* as = stage_of(0);
-#pragma unroll
-    for (int r = 0; r < kReads; ++r) fetch(0, as, as + BM * kRowBytes, 0, r);
+    reader_a.at(lds_address(0), next_a);
+    reader_b.at(lds_address(0) + BM * kRowBytes, next_b);
+    static_for<kReads>([&](auto r) { fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, r, next_a, next_b); });
   }
 
   for (int t = 0; t < n; ++t) {
-    const char* as = stage_of(t);
-    const char* bs = as + BM * kRowBytes;
-    const char* as_next = stage_of(t + 1);
-    const char* bs_next = as_next + BM * kRowBytes;
     const bool more = t + 1 < n;
-#pragma unroll
-    for (int blk = 0; blk < NB; ++blk) {
-      const int cur = blk & 1, nxt = cur ^ 1;
-      const bool last = blk == NB - 1;
+    reader_a.at(lds_address(t), at_a);
+    reader_b.at(lds_address(t) + BM * kRowBytes, at_b);
+    const char* as = stage_of(t);
+    static_for<NB>([&](auto blk_c) {
+      constexpr int blk = decltype(blk_c)::value;
+      constexpr int cur = blk & 1, nxt = cur ^ 1;
+      constexpr bool last = blk == NB - 1;
       // ---- the fragments of this block are in registers
       lds_done();
       keep(cur);
@@ -759,7 +854,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
           }
         }
       }
-      if (last) {
+      if constexpr (last) {
         // All of tile t is in registers; this wave's loads of tile t + 1 have landed (tile t + 2, when the ring
         // has three stages, may stay in flight).
         if (STAGES == 3 && t + 2 < n) __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoadsPerTile, 15));
@@ -768,33 +863,30 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
+        reader_a.at(lds_address(t + 1), next_a);
+        reader_b.at(lds_address(t + 1) + BM * kRowBytes, next_b);
       }
       pin();
       // ---- MFMAs of this block; between them the next block's fragment reads and one part of a later tile's loads
-      const char* ra = last ? as_next : as;
-      const char* rb = last ? bs_next : bs;
-      const int kg_next = last ? 0 : (blk + 1) * KGB;
+      constexpr int kg_next = last ? 0 : (blk + 1) * KGB;
       const bool fetching = !last || more;
       const int load_tile = last ? t + STAGES : t + STAGES - 1;   // part 0 right after the barrier, the others in the next tile's blocks
-      const int load_part = last ? 0 : blk + 1;
-#pragma unroll
-      for (int g = 0; g < KGB; ++g) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            const int idx = (g * TM + i) * TN + j;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[cur][g * TM + i]),
-                                                                __builtin_bit_cast(bf16x8, fb[cur][g * TN + j]), acc[i][j], 0, 0, 0);
-            if (fetching) {
-#pragma unroll
-              for (int r = idx * kReadsPerSlot; r < (idx + 1) * kReadsPerSlot; ++r) fetch(nxt, ra, rb, kg_next, r);
-            }
-            if (idx == 0 && load_part < PARTS) issue_part(load_tile, load_part);
-            pin();
-          }
+      constexpr int load_part = last ? 0 : blk + 1;
+      static_for<kMfma>([&](auto idx_c) {
+        constexpr int idx = decltype(idx_c)::value;
+        constexpr int g = idx / (TM * TN), i = (idx / TN) % TM, j = idx % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[cur][g * TM + i]),
+                                                            __builtin_bit_cast(bf16x8, fb[cur][g * TN + j]), acc[i][j], 0, 0, 0);
+        if (fetching) {
+          static_for<kReadsPerSlot>([&](auto q) {
+            constexpr int r = idx * kReadsPerSlot + decltype(q)::value;
+            if constexpr (last) fetch(std::integral_constant<int, nxt>{}, std::integral_constant<int, kg_next>{}, std::integral_constant<int, r>{}, next_a, next_b);
+            else fetch(std::integral_constant<int, nxt>{}, std::integral_constant<int, kg_next>{}, std::integral_constant<int, r>{}, at_a, at_b);
+          });
         }
-      }
+        if constexpr (idx == 0 && load_part < PARTS) issue_part(load_tile, load_part);
+        pin();
+      });
       if constexpr (LA == Layout::KRow) {
         if (blk == 0 && want_row_sum) {
 #pragma unroll
@@ -806,7 +898,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
           pin();
         }
       }
-    }
+    });
   }
   lds_done();
   // Every wave is past the last tile's barrier, which it reached with the whole tile in registers: the ring is dead.
