@@ -718,17 +718,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 // the tile in registers (so the buffer may be overwritten: tile t + STAGES goes there, its parts issued in the
 // blocks that follow) and knows its own loads of tile t + 1 have landed (so everybody may read it: the last block
 // fetches tile t + 1's first fragments).
-//   STAGES = 3: a tile's loads in 4 parts; they have a whole tile's time to land.
+//   STAGES >= 3: a tile's loads in as many parts as the tile has blocks; they have STAGES - 2 tiles' time to land
+//   (the tile being multiplied plus STAGES - 2 tiles may be on their way).
 //   STAGES = 2 (tiles too large for three): 2 parts, in the block after the barrier and the one after that, which
 //   leaves them two blocks to land.
 template <int BM, int BN, int STAGES, int WAVES_M, int WAVES_N, int KGB, Layout LA, Layout LB, Gather GA, Gather GB>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(GemmParams p) {
   constexpr int NW = WAVES_M * WAVES_N;
   static_assert(NW == 4 || NW == 8, "four or eight wavefronts per workgroup");
-  static_assert(STAGES == 2 || STAGES == 3, "ring depth");
+  static_assert(STAGES >= 2 && STAGES <= 5, "ring depth");
   static_assert(KGB == 1 || KGB == 2, "k-groups per block");
   constexpr int NB = 4 / KGB;                          // blocks per tile
-  constexpr int PARTS = STAGES == 3 ? NB : NB / 2;     // a tile's loads: in every block, or in the two after the barrier
+  constexpr int PARTS = STAGES >= 3 ? NB : NB / 2;     // a tile's loads: in every block, or in the two after the barrier
   static_assert(PARTS >= 1, "a ring of two stages needs four blocks per tile");
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -740,7 +741,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
   using SourceA = TileSource<BM, LA, GA, NW>;
   using SourceB = TileSource<BN, LB, GB, NW>;
   constexpr int kLoadsPerTile = SourceA::kInstr + SourceB::kInstr;
-  static_assert(kLoadsPerTile < 64, "vmcnt range");
+  static_assert((STAGES - 2) * kLoadsPerTile < 64, "vmcnt range");
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   int tile_m, tile_n;
@@ -855,9 +856,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
         }
       }
       if constexpr (last) {
-        // All of tile t is in registers; this wave's loads of tile t + 1 have landed (tile t + 2, when the ring
-        // has three stages, may stay in flight).
-        if (STAGES == 3 && t + 2 < n) __builtin_amdgcn_s_waitcnt(waitcnt_imm(kLoadsPerTile, 15));
+        // All of tile t is in registers; this wave's loads of tile t + 1 have landed (the STAGES - 2 tiles after it may
+        // stay in flight when all of them have been issued).
+        if (STAGES >= 3 && t + STAGES - 1 < n) __builtin_amdgcn_s_waitcnt(waitcnt_imm((STAGES - 2) * kLoadsPerTile, 15));
         else __builtin_amdgcn_s_waitcnt(waitcnt_imm(0, 15));
         pin();
         asm volatile("" ::: "memory");
@@ -1190,13 +1191,13 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   // 128 x 128 workgroups per CU)
   if (q.M >= 256 && q.N >= 256 && q.K > 128 && t256 >= 176 && (t256 <= 256 || t256 >= 448)) return launch_tile_pipe<256, 256, 2, 2, 4, 1, LA, LB, GA, GB>(q, stream);
   // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
-  // alone on its CU needs a third stage in flight instead.
+  // alone on its CU keeps three tiles in flight instead (a four-stage ring; a fifth stage measured slower).
   if (tiles(128, 128) > 256) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
   if (tiles(128, 128) >= 192) {
     // one round of lone workgroups: convolutions (gathered operands) did 2-5 % better as two 128 x 64 workgroups per
     // CU; plain products were level, and 128 x 128 leaves LDS for a weight-gradient workgroup of the second stream
     if constexpr (GA != Gather::None || GB != Gather::None) return launch_tile<128, 64, 3, 4, 1, LA, LB, GA, GB>(q, stream);
-    else return launch_tile_pipe<128, 128, 3, 2, 4, 2, LA, LB, GA, GB>(q, stream);   // eight waves: a lone workgroup needs two per SIMD to hide its own latencies
+    else return launch_tile_pipe<128, 128, 4, 2, 4, 2, LA, LB, GA, GB>(q, stream);   // eight waves: a lone workgroup needs two per SIMD to hide its own latencies
   }
   // 64 x 64: the ring depth that lets every tile be resident at once (two or three workgroups per CU).
   if (tiles(64, 64) > 512) return launch_tile<64, 64, 3, 2, 2, LA, LB, GA, GB>(q, stream);
