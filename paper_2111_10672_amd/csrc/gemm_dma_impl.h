@@ -17,6 +17,7 @@
 // Tile loop: wait for tile t (s_waitcnt vmcnt leaves the younger tiles' loads in flight), one barrier,
 // issue tile t + STAGES - 1 into the buffer tile t - 1 used, multiply tile t.
 #pragma once
+#include <type_traits>
 #include "gemm_common.h"
 
 namespace spb {
@@ -568,19 +569,188 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
   }
 }
 
+// Epilogue of the large kernels.  Their tile loops multiply with the operands exchanged (the N-side fragment is the
+// MFMA's first operand), so the 16 accumulators a lane holds of a 32 x 32 block are 16 columns of ONE output row:
+// row = lane % 32, column = 8 * (r / 4) + 4 * (lane / 32) + r % 4.  Four consecutive registers are four consecutive
+// columns, so a wave parks 32 rows of its tile in its own LDS region (the tile ring is dead by then) with one
+// 16-byte write per four accumulators, and reads them back so that consecutive lanes hold consecutive 16-byte
+// pieces of a row: loads of the per-element tensor and stores of the result are whole 64-byte segments per four
+// lanes (stores scattered one lane per row were measured 2-3 x slower: every lane becomes a request of its own at the
+// L2).  LDS operations of one wave complete in order, so no barrier separates the pieces.  A wave issues about 1.7 k
+// instructions at 4 cycles each if this is written as a loop over rows with the mode tested per element (8 us per
+// product, as much as 12 k-tiles of the tile loop); hence: the row loop is unrolled with the mode decided outside
+// it, a lane's column and its per-column operands never change, a row's address is the previous one plus a constant,
+// and the per-element chunks of the next 32 rows are requested before the current ones are stored, so waiting for
+// them never waits for a store.  The arithmetic per element is that of store_rows_bf16.
 template <int WM, int WN>
-__device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage,
-                                                int row_base, int col_base, int lane, long long c_offset) {
-  constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of rows 4 apart
+__device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage, int row_base, int col_base, int lane, long long c_offset) {
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of consecutive rows
+  float* park_at = stage + (lane & 31) * kPitch + 4 * (lane >> 5);
+  auto park = [&](int i) {
 #pragma unroll
-  for (int piece = 0; piece < WM / 32; ++piece) {
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int j = 0; j < WN / 32; ++j)
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<f32x4*>(park_at + j * 32 + 8 * g) = f32x4{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+  };
+  if (p.epilogue == (int)Epilogue::StoreF32) {
+    constexpr int kPerRow = WN / 4, kRowStep = 64 / kPerRow, kIters = (32 + kRowStep - 1) / kRowStep;
+    const int c = (lane % kPerRow) * 4, n = col_base + c, row0 = lane / kPerRow;
+    const bool active = n < p.N && lane < kPerRow * kRowStep, whole = n + 4 <= p.N;
+    f32x4 b = {0.f, 0.f, 0.f, 0.f};
+    if (p.bias && whole) {
+      const uint2 bb = *reinterpret_cast<const uint2*>(static_cast<const bf16_t*>(p.bias) + n);
+      b[0] = __uint_as_float(bb.x << 16); b[1] = __uint_as_float(bb.x & 0xFFFF0000u);
+      b[2] = __uint_as_float(bb.y << 16); b[3] = __uint_as_float(bb.y & 0xFFFF0000u);
+    }
+    const float* from = stage + row0 * kPitch + c;
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + j * 32 + (lane & 31)] = acc[piece][j][r];
-    if (p.epilogue == (int)Epilogue::StoreF32) store_rows_f32<WN>(p, stage, row_base + piece * 32, col_base, lane, c_offset);
-    else store_rows_bf16<WN>(p, stage, row_base + piece * 32, col_base, lane, c_offset);
+    for (int i = 0; i < TM; ++i) {
+      park(i);
+      if (!active) continue;
+      float* to = static_cast<float*>(p.C) + c_offset + (size_t)(row_base + i * 32 + row0) * p.ldc + n;
+#pragma unroll
+      for (int it = 0; it < kIters; ++it) {
+        const int row = row0 + it * kRowStep, m = row_base + i * 32 + row;
+        if (row >= 32 || m >= p.M) break;
+        const f32x4 v = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch);
+        if (whole) {
+          *reinterpret_cast<f32x4*>(to + (size_t)it * kRowStep * p.ldc) = v * p.alpha + b;
+        } else {
+          float t[4] = {v[0], v[1], v[2], v[3]};
+          store_ragged(p, t, 4, m, n, c_offset);
+        }
+      }
+    }
+    return;
+  }
+  constexpr int kPerRow = WN / 8, kRowStep = 64 / kPerRow, kIters = (32 + kRowStep - 1) / kRowStep;
+  const int c = (lane % kPerRow) * 8, n = col_base + c, row0 = lane / kPerRow;
+  const bool active = n < p.N && lane < kPerRow * kRowStep, whole = n + 8 <= p.N;
+  const int mode = p.epilogue;
+  const bool plain = mode == (int)Epilogue::BiasAct;
+  bf16_t* aux = plain ? static_cast<bf16_t*>(p.aux_out) : nullptr;
+  const bf16_t* xsrc = plain ? static_cast<const bf16_t*>(p.residual) : static_cast<const bf16_t*>(p.mask);
+  const int ldx = plain ? p.ldres : p.ldmask;
+  const int last_row = p.M - 1;
+  const bool scaled = p.alpha != 1.f;
+  const float* from = stage + row0 * kPitch + c;
+  auto request = [&](int i, u32x4 (&dst)[kIters]) {
+    if (xsrc == nullptr || !active || !whole) return;
+#pragma unroll
+    for (int it = 0; it < kIters; ++it)  // from a clamped, always valid row
+      dst[it] = *reinterpret_cast<const u32x4*>(xsrc + (size_t)min(row_base + i * 32 + row0 + it * kRowStep, last_row) * ldx + n);
+  };
+  // math(v, x, pre): v = alpha * acc on entry and the result on return; x = the per-element tensor's 8 values (only
+  // with has_x); pre = what the auxiliary output stores (only worked out with has_aux).  Both flags are template
+  // arguments of the variant so that a product without those tensors spends no instruction on them.
+  auto run = [&](auto has_x, auto has_aux, auto&& math) {
+    constexpr bool kX = decltype(has_x)::value, kAux = decltype(has_aux)::value;
+    u32x4 xs[2][kIters];
+    if constexpr (kX) request(0, xs[0]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      park(i);
+      if constexpr (kX) { if (i + 1 < TM) request(i + 1, xs[(i + 1) & 1]); }
+      if (!active) continue;
+      if (!whole) {  // ragged right edge: element by element
+#pragma unroll 1
+        for (int row = row0; row < 32 && row_base + i * 32 + row < p.M; row += kRowStep) {
+          float t[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) t[e] = stage[row * kPitch + c + e];
+          store_ragged(p, t, 8, row_base + i * 32 + row, n, c_offset);
+        }
+        continue;
+      }
+      const size_t first = (size_t)(row_base + i * 32 + row0);
+      bf16_t* to = static_cast<bf16_t*>(p.C) + c_offset + first * p.ldc + n;
+      bf16_t* to_aux = kAux ? aux + first * p.ldaux + n : nullptr;
+#pragma unroll
+      for (int it = 0; it < kIters; ++it) {
+        const int row = row0 + it * kRowStep;
+        if (row >= 32 || row_base + i * 32 + row >= p.M) break;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch + 4);
+        float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]}, x[8], pre[8];
+        if (scaled) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= p.alpha;
+        }
+        if constexpr (kX) unpack_bf16x8(xs[i & 1][it], x);
+        math(has_x, has_aux, v, x, pre);
+        if constexpr (kAux) *reinterpret_cast<u32x4*>(to_aux + (size_t)it * kRowStep * p.ldaux) = pack_bf16x8(pre);
+        *reinterpret_cast<u32x4*>(to + (size_t)it * kRowStep * p.ldc) = pack_bf16x8(v);
+      }
+    }
+  };
+  using Yes = std::true_type;
+  using No = std::false_type;
+  if (mode == (int)Epilogue::MaskStore) {
+    run(Yes{}, No{}, [](auto, auto, float (&v)[8], const float (&x)[8], float (&)[8]) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = x[e] > 0.f ? v[e] : 0.f;
+    });
+    return;
+  }
+  if (mode == (int)Epilogue::ScaleStore) {
+    run(Yes{}, No{}, [](auto, auto, float (&v)[8], const float (&x)[8], float (&)[8]) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] *= x[e];
+    });
+    return;
+  }
+  ColumnOperands cols;
+  load_column_operands<WN>(p, col_base, lane, cols);
+  float sc[8], bs[8];
+  unpack_bf16x8(cols.sc, sc);
+  unpack_bf16x8(cols.bs, bs);
+  const bool aux_raw = p.aux_raw != 0;
+  // v = v * s + b; pre = that (or the unscaled product); a residual joins before the activation
+  auto affine = [&](auto has_x, auto has_aux, float (&v)[8], const float (&x)[8], float (&pre)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float t = v[e] * sc[e] + bs[e];
+      if constexpr (decltype(has_aux)::value) pre[e] = aux_raw ? v[e] : t;
+      if constexpr (decltype(has_x)::value) v[e] = t + x[e];
+      else v[e] = t;
+    }
+  };
+  // the four combinations of (residual, auxiliary output) of one activation
+  auto variants = [&](auto&& math) {
+    if (xsrc != nullptr) {
+      if (aux != nullptr) run(Yes{}, Yes{}, math);
+      else run(Yes{}, No{}, math);
+    } else {
+      if (aux != nullptr) run(No{}, Yes{}, math);
+      else run(No{}, No{}, math);
+    }
+  };
+  if (p.act == (int)Act::Relu) {
+    variants([&](auto has_x, auto has_aux, float (&v)[8], const float (&x)[8], float (&pre)[8]) {
+      affine(has_x, has_aux, v, x, pre);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+    });
+  } else if (p.act == (int)Act::Gelu) {
+    if (p.aux_act_grad && aux != nullptr) {  // the auxiliary output takes the activation's derivative
+      auto both = [&](auto has_x, auto, float (&v)[8], const float (&x)[8], float (&pre)[8]) {
+        affine(has_x, No{}, v, x, pre);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gelu_both_f(v[e], v[e], pre[e]);
+      };
+      if (xsrc != nullptr) run(Yes{}, Yes{}, both);
+      else run(No{}, Yes{}, both);
+    } else {
+      variants([&](auto has_x, auto has_aux, float (&v)[8], const float (&x)[8], float (&pre)[8]) {
+        affine(has_x, has_aux, v, x, pre);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+      });
+    }
+  } else {
+    variants(affine);
   }
 }
 
@@ -665,8 +835,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[g * TM + i]),
-                                                                __builtin_bit_cast(bf16x8, b[g * TN + j]), acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, b[g * TN + j]),   // operands exchanged:
+                                                                __builtin_bit_cast(bf16x8, a[g * TM + i]), acc[i][j], 0, 0, 0);  // see store_wave_tile
       if constexpr (LA == Layout::RowK && LB == Layout::RowK) {
         // Keep the batch's LDS reads ahead of its MFMAs (the scheduler otherwise sinks each read to its use
         // and the wave eats one LDS latency per MFMA).
@@ -737,12 +907,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
   constexpr int kMfma = KGB * TM * TN, kReads = KGB * (TM + TN);   // per block
   constexpr int kReadsPerSlot = (kReads + kMfma - 1) / kMfma;
   constexpr int kStageBytes = (BM + BN) * kRowBytes;
-  static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
   using SourceA = TileSource<BM, LA, GA, NW>;
   using SourceB = TileSource<BN, LB, GB, NW>;
   constexpr int kLoadsPerTile = SourceA::kInstr + SourceB::kInstr;
   static_assert((STAGES - 2) * kLoadsPerTile < 64, "vmcnt range");
 
+  static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   int tile_m, tile_n;
   xcd_tile_grouped(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
@@ -876,8 +1046,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
       static_for<kMfma>([&](auto idx_c) {
         constexpr int idx = decltype(idx_c)::value;
         constexpr int g = idx / (TM * TN), i = (idx / TN) % TM, j = idx % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[cur][g * TM + i]),
-                                                            __builtin_bit_cast(bf16x8, fb[cur][g * TN + j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][g * TN + j]),   // operands exchanged:
+                                                            __builtin_bit_cast(bf16x8, fa[cur][g * TM + i]), acc[i][j], 0, 0, 0);  // see store_wave_tile
         if (fetching) {
           static_for<kReadsPerSlot>([&](auto q) {
             constexpr int r = idx * kReadsPerSlot + decltype(q)::value;
