@@ -151,15 +151,41 @@ __global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __rest
 // Backward of the same attention, one workgroup per (batch entry, head):
 //   dP = dctx V^T;  dS = P * (dP - rowsum(dP * P)) * scale (rounded to bfloat16, as the unfused path stores it);
 //   dQ = dS K;  dK = dS^T Q;  dV = P^T dctx.
-// Phase 1 is row-wise: wave w forms dP and dS of its 32 queries in the accumulator layout (P comes straight from
-// HBM in that layout) and parks dS twice, as the RowK tiles its own dQ product reads and into a workgroup-wide KRow
-// tile (k = query) that dK reads.  After one barrier, phase 2: wave w produces rows 32 w .. of dQ, dK and dV, three
+// Phase 1 is row-wise: wave w forms dP and dS of its 32 queries in the accumulators (P comes straight from HBM in
+// that layout) and writes dS once, into a workgroup-wide KRow tile (k = query) that dK reads; its own dQ product
+// takes dS from the registers.  After one barrier, phase 2: wave w produces rows 32 w .. of dQ, dK and dV, three
 // products of 16 MFMAs each, with K, Q and dctx read through transposing LDS reads and P as a KRow tile that came
-// in by direct-to-LDS loads.  LDS: dctx twice (RowK for dP, KRow for dV), V (RowK), K, Q (KRow), P (KRow) and
-// the two dS copies; the KRow dS tile takes over the space of dctx-RowK and V once dP is done.
+// in by direct-to-LDS loads.  LDS: dctx twice (RowK for dP, KRow for dV), V (RowK), K, Q (KRow), P (KRow), the KRow dS
+// tile, which takes over the space of dctx-RowK and V once dP is done, and 8 KB per wave through which results leave.
 constexpr int kDsK = kSeqMax * 2 * kSeqMax;  // dS as KRow tiles: two k tiles of 64 queries x 128 key rows
 constexpr int kBwdLds = kQBytes /*dctx RowK*/ + kQBytes /*V RowK*/ + 3 * kVBytes /*dctx, K, Q as KRow*/ + kDsK /*P KRow*/ + 4 * kPWave;
 static_assert(2 * kQBytes == kDsK, "the KRow dS tile reuses the dctx and V tiles of phase 1");
+
+// Rotation of the KRow dS tile (see the kernel): by 2 chunks per k-row, modulo 8 k-rows.
+__device__ __forceinline__ int dsk_rot(int k) { return (k & 7) << 1; }
+
+// One MFMA operand out of a KRow tile, like read_fragment, with two options: OWN_ROT reads a tile laid out with
+// dsk_rot instead of the loader's rotation; SPLIT_K fetches, for half-wave hh, k = 16 kg + 4 hh + (0..3) and
+// 16 kg + 8 + 4 hh + (0..3) instead of 16 kg + 8 hh + (0..7), the order of k of an A fragment that comes straight
+// from exchanged-operand accumulators.  Valid only after fragments_ready().
+template <int ROWS, bool OWN_ROT, bool SPLIT_K>
+__device__ __forceinline__ u32x4 read_krow(const char* tile, int frag_row0, int kg, int lane) {
+  constexpr int kRowChunks = ROWS / 8;
+  const int j = lane & 15, g = lane >> 4;
+  const int row = frag_row0 + 16 * (g & 1) + 4 * (j & 3);
+  u32x4 out;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int k = 16 * kg + (SPLIT_K ? 4 * (g >> 1) + 8 * h : 8 * (g >> 1) + 4 * h) + (j >> 2);
+    const int pc = ((row >> 3) + (OWN_ROT ? dsk_rot(k) : krow_rot<ROWS>(k))) % kRowChunks;
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_ptr_t)(tile + k * (ROWS * 2) + pc * 16 + (row & 7) * 2);
+    uint2 w;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(w) : "v"(lds_addr));
+    out[2 * h] = w.x;
+    out[2 * h + 1] = w.y;
+  }
+  return out;
+}
 
 __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __restrict__ qkv, int ld_qkv, const bf16_t* __restrict__ prob,
                                                             const bf16_t* __restrict__ dctx, int ld_ctx, bf16_t* __restrict__ dqkv,
@@ -174,7 +200,7 @@ __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __rest
   char* p_k = q_k + kVBytes;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  char* ds_r = p_k + kDsK + wave * kPWave;      // this wave's dS as RowK tiles (two k tiles of 64 keys x 32 rows)
+  char* out_stage = p_k + kDsK + wave * kPWave;   // this wave's 32 x 64 floats on their way out
   const int z = blockIdx.x, b = z / heads, h = z - b * heads;
   const int hidden = heads * kHeadDim;
   const bf16_t* base = qkv + (size_t)b * seq * ld_qkv + h * kHeadDim;
@@ -202,19 +228,30 @@ __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __rest
       src_p.issue(t, seq, p_k + t * (kSeqMax * kRowBytes), wave, seq, none);
     }
   }
-  // P of this wave's rows in the accumulator layout, straight from HBM, while the tiles are in flight
-  const int key0 = lane & 31, q0 = 32 * wave;
-  float pv[4][16];
+  // P of this wave's queries, four consecutive keys at a time, straight from HBM while the tiles are in flight.
+  // Phase 1 multiplies with the MFMA operands exchanged, so lane l holds, of query q0 + l % 32, the keys
+  // 32 j + 8 (r / 4) + 4 (l / 32) + r % 4 of key block j: a query's row lies in two lanes (one exchange for the row
+  // sum instead of a shuffle tree per register), four consecutive registers are four consecutive keys (8-byte loads
+  // of P, 8-byte LDS writes of dS), and eight consecutive registers are, up to the order of k, an A fragment of
+  // dQ = dS K, which therefore never goes through LDS.
+  const int q0 = 32 * wave, qi = lane & 31, hh = lane >> 5, q = q0 + qi;
+  // Requested as 16-byte pieces (keys 8 c .. 8 c + 7), the lower half-wave the even c and the upper the odd ones;
+  // two v_permlane32_swap per pair of pieces then hand each lane its half of both.
+  u32x4 praw[8];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int q = q0 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int key = 32 * j + key0;
-      pv[j][r] = (q < seq && key < seq) ? to_float(pz[(size_t)q * seq + key]) : 0.f;
-    }
+  for (int m = 0; m < 8; ++m) {
+    const int key = 8 * (2 * m + hh);
+    praw[m] = (q < seq && key < seq) ? *reinterpret_cast<const u32x4*>(pz + (size_t)q * seq + key) : u32x4{0u, 0u, 0u, 0u};
   }
   wait_loads_and_barrier<0>();
+  uint2 pw[4][4];   // pw[j][g]: keys 32 j + 8 g + 4 hh + (0..3)
+#pragma unroll
+  for (int m = 0; m < 8; ++m) {
+    const auto x = __builtin_amdgcn_permlane32_swap(praw[m][0], praw[m][2], false, false);
+    const auto y = __builtin_amdgcn_permlane32_swap(praw[m][1], praw[m][3], false, false);
+    pw[m >> 1][2 * (m & 1)] = uint2{x[0], y[0]};
+    pw[m >> 1][2 * (m & 1) + 1] = uint2{x[1], y[1]};
+  }
 
   // phase 1: dP = dctx V^T for this wave's queries
   f32x16 dp[4];
@@ -228,64 +265,74 @@ __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __rest
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const u32x4 vb = read_fragment<kSeqMax, Layout::RowK>(v_r, 32 * j, g, lane);
-      dp[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, vb), dp[j], 0, 0, 0);
+      dp[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vb), __builtin_bit_cast(bf16x8, a), dp[j], 0, 0, 0);
     }
   }
-  // dS, rounded to bfloat16, kept in registers until every wave is done with the phase-1 tiles
-  uint16_t ds_bits[4][16];
+  // dS, rounded to bfloat16 and packed two keys to a word: ds[j][4 g + e] holds keys 32 j + 8 g + 4 hh + 2 e, + 1
+  uint32_t ds[4][8];
+  {
+    float pv[4][16];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        pv[j][4 * g] = __uint_as_float(pw[j][g].x << 16); pv[j][4 * g + 1] = __uint_as_float(pw[j][g].x & 0xFFFF0000u);
+        pv[j][4 * g + 2] = __uint_as_float(pw[j][g].y << 16); pv[j][4 * g + 3] = __uint_as_float(pw[j][g].y & 0xFFFF0000u);
+      }
     float dot = 0.f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dot += dp[j][r] * pv[j][r];
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int o = 16; o > 0; o >>= 1) dot += __shfl_xor(dot, o, 64);
+      for (int r = 0; r < 16; ++r) dot += dp[j][r] * pv[j][r];
+    dot += __shfl_xor(dot, 32, 64);   // the other half of the row
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bf16_t v;
-      store_elem(&v, pv[j][r] * (dp[j][r] - dot) * scale);
-      ds_bits[j][r] = v.bits;
-    }
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        ds[j][e] = pack_bf16(pv[j][2 * e] * (dp[j][2 * e] - dot) * scale, pv[j][2 * e + 1] * (dp[j][2 * e + 1] - dot) * scale);
   }
   __syncthreads();  // all waves have read dctx_r and v_r: their space becomes the KRow dS tile
+  // dS as KRow tiles (k = query, rows = keys) for dK = dS^T Q: two k tiles of 64 queries, 128 key rows of 2 bytes per
+  // k-row, the 16-byte chunks of k-row kk rotated by 2 (kk % 8), which keeps these 8-byte writes (32 k-rows at once)
+  // and the transposing reads below (4 k-rows at once) off each other's banks.
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);   // query within the wave
-    const int q = q0 + row;
+  for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int key = 32 * j + key0;
-      // RowK copy (rows = this wave's queries, k = key)
-      *reinterpret_cast<uint16_t*>(ds_r + (key >> 6) * (32 * kRowBytes) + lds_offset(row, (key & 63) >> 3) + (key & 7) * 2) = ds_bits[j][r];
-      // KRow copy (k = query, rows = keys): k tile q / 64, k-row q % 64, 128 rows of 2 bytes with the tile's chunk rotation
-      const int kk = q & 63;
-      const int pc = ((key >> 3) + krow_rot<kSeqMax>(kk)) & (kSeqMax / 8 - 1);
-      *reinterpret_cast<uint16_t*>(ds_k + (q >> 6) * (kSeqMax * kRowBytes) + kk * (kSeqMax * 2) + pc * 16 + (key & 7) * 2) = ds_bits[j][r];
+    for (int g = 0; g < 4; ++g) {
+      const int key = 32 * j + 8 * g + 4 * hh, kk = q & 63;
+      const int pc = ((key >> 3) + dsk_rot(kk)) & (kSeqMax / 8 - 1);
+      *reinterpret_cast<uint2*>(ds_k + (q >> 6) * (kSeqMax * kRowBytes) + kk * (kSeqMax * 2) + pc * 16 + (key & 7) * 2) = uint2{ds[j][2 * g], ds[j][2 * g + 1]};
     }
-  }
   __syncthreads();
 
-  // phase 2: three [32 x 64] outputs per wave; each goes out through the wave's own staging rows
-  float* stage = reinterpret_cast<float*>(ds_r);   // reused after dQ has read ds_r (LDS operations of a wave run in order)
+  // phase 2: three [32 x 64] outputs per wave, multiplied with the operands exchanged so that four consecutive
+  // accumulators are four consecutive features of one row: a result parks in the wave's staging rows with 16-byte
+  // writes (the 16 chunks of a 256-byte row permuted by row % 16, which keeps both the writes, 32 rows at once, and
+  // the row-wise reads off each other's banks) and leaves as whole 128-byte rows.
+  float* stage = reinterpret_cast<float*>(out_stage);
   constexpr int kPitch = kHeadDim;
   auto write_out = [&](f32x16 (&o)[2], int col_block) {
     asm volatile("" ::: "memory");
+    const int prow = lane & 31;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int n = 0; n < 2; ++n)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + 32 * j + (lane & 31)] = o[j][r];
+      for (int g = 0; g < 4; ++g) {
+        const int chunk = (8 * n + 2 * g + hh) ^ (prow & 15);
+        *reinterpret_cast<f32x4*>(stage + prow * kPitch + chunk * 4) = f32x4{o[n][4 * g], o[n][4 * g + 1], o[n][4 * g + 2], o[n][4 * g + 3]};
+      }
     asm volatile("" ::: "memory");
     bf16_t* out = dqkv + (size_t)b * seq * ld_qkv + col_block * hidden + h * kHeadDim;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const int row = it * 8 + (lane >> 3), c = (lane & 7) * 8;
+      const int row = it * 8 + (lane >> 3), c = (lane & 7) * 2;
       if (q0 + row < seq) {
         float v[8];
-        const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c), v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + (c ^ (row & 15)) * 4);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + ((c + 1) ^ (row & 15)) * 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
-        *reinterpret_cast<u32x4*>(out + (size_t)(q0 + row) * ld_qkv + c) = pack_bf16x8(v);
+        *reinterpret_cast<u32x4*>(out + (size_t)(q0 + row) * ld_qkv + c * 4) = pack_bf16x8(v);
       }
     }
     asm volatile("" ::: "memory");
@@ -297,20 +344,23 @@ __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __rest
       for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
   };
   f32x16 acc[2];
-  // dQ[q, d] = sum_key dS[q, key] K[key, d]
+  // dQ[q, d] = sum_key dS[q, key] K[key, d]: the A fragment of k-group g of key tile kt is ds[2 kt + g / 2][4 (g % 2) ..],
+  // whose two half-waves hold keys 16 g + 4 hh + (0..3) and 16 g + 8 + 4 hh + (0..3); K's fragments are fetched in the
+  // same order of k.
   zero(acc);
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       u32x4 a[1], bb[2];
-      a[0] = read_fragment<32, Layout::RowK>(ds_r + kt * (32 * kRowBytes), 0, g, lane);
-      bb[0] = read_fragment<kHeadDim, Layout::KRow>(k_k + kt * (kHeadDim * kRowBytes), 0, g, lane);
-      bb[1] = read_fragment<kHeadDim, Layout::KRow>(k_k + kt * (kHeadDim * kRowBytes), 32, g, lane);
+      const int j = 2 * kt + (g >> 1), e0 = 4 * (g & 1);
+      a[0] = u32x4{ds[j][e0], ds[j][e0 + 1], ds[j][e0 + 2], ds[j][e0 + 3]};
+      bb[0] = read_krow<kHeadDim, false, true>(k_k + kt * (kHeadDim * kRowBytes), 0, g, lane);
+      bb[1] = read_krow<kHeadDim, false, true>(k_k + kt * (kHeadDim * kRowBytes), 32, g, lane);
       fragments_ready(a, bb);
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[0]), __builtin_bit_cast(bf16x8, bb[j]), acc[j], 0, 0, 0);
+      for (int n = 0; n < 2; ++n)
+        acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bb[n]), __builtin_bit_cast(bf16x8, a[0]), acc[n], 0, 0, 0);
     }
   write_out(acc, 0);
   // dK[key, d] = sum_q dS[q, key] Q[q, d]   and   dV[key, d] = sum_q P[q, key] dctx[q, d]: rows = this wave's 32 keys
@@ -324,13 +374,14 @@ __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __rest
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         u32x4 a[1], bb[2];
-        a[0] = read_fragment<kSeqMax, Layout::KRow>(a_tile + kt * (kSeqMax * kRowBytes), q0, g, lane);
+        a[0] = which == 0 ? read_krow<kSeqMax, true, false>(a_tile + kt * (kSeqMax * kRowBytes), q0, g, lane)
+                          : read_fragment<kSeqMax, Layout::KRow>(a_tile + kt * (kSeqMax * kRowBytes), q0, g, lane);
         bb[0] = read_fragment<kHeadDim, Layout::KRow>(b_tile + kt * (kHeadDim * kRowBytes), 0, g, lane);
         bb[1] = read_fragment<kHeadDim, Layout::KRow>(b_tile + kt * (kHeadDim * kRowBytes), 32, g, lane);
         fragments_ready(a, bb);
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[0]), __builtin_bit_cast(bf16x8, bb[j]), acc[j], 0, 0, 0);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, bb[j]), __builtin_bit_cast(bf16x8, a[0]), acc[j], 0, 0, 0);
       }
     write_out(acc, 1 + which);
   }
