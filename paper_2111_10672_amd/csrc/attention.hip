@@ -6,8 +6,9 @@
 // values feed the second product, as in the unfused path).
 //
 // Four waves, each owning 32 query rows from start to end: after the one barrier that publishes the tiles no wave
-// waits for another.  Row-wise maximum and sum run over the accumulator layout (a row lives in the 32 lanes of one
-// half-wave, 4 tiles wide), P is parked per wave in LDS in the layout the second product's A fragments read.
+// waits for another.  Both products run with the MFMA operands exchanged, which puts a query's row of scores into
+// two lanes (row-wise maximum and sum need one exchange) and lets the second product take P from the registers;
+// P passes through LDS only on its way to HBM.
 #include "gemm_dma_impl.h"
 
 namespace spb {
@@ -19,147 +20,6 @@ constexpr int kQBytes = kSeqMax * kRowBytes;          // Q tile, RowK: 128 rows 
 constexpr int kVBytes = 2 * kHeadDim * kRowBytes;     // V, KRow: two k tiles (64 keys each) x 64 feature rows
 constexpr int kPWave = 2 * 32 * kRowBytes;            // one wave's P: two k tiles (64 keys each) x 32 query rows
 constexpr int kAttnLds = 2 * kQBytes + kVBytes + 4 * kPWave;
-
-__global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __restrict__ qkv, int ld_qkv, bf16_t* __restrict__ prob,
-                                                            bf16_t* __restrict__ ctx, int ld_ctx, int heads, int seq, float scale) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  char* q_tile = lds;
-  char* k_tile = lds + kQBytes;
-  char* v_tile = lds + 2 * kQBytes;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  char* p_tile = lds + 2 * kQBytes + kVBytes + wave * kPWave;
-  const int z = blockIdx.x, b = z / heads, h = z - b * heads;
-  const int hidden = heads * kHeadDim;
-  const bf16_t* base = qkv + (size_t)b * seq * ld_qkv + h * kHeadDim;
-  ConvGeom none{};
-
-  TileSource<kSeqMax, Layout::RowK, Gather::None, 4> src_q, src_k;
-  TileSource<kHeadDim, Layout::KRow, Gather::None, 4> src_v;
-  src_q.init(base, ld_qkv, 0, seq, wave, lane, 0, none);
-  src_k.init(base + hidden, ld_qkv, 0, seq, wave, lane, 0, none);
-  src_v.init(base + 2 * hidden, ld_qkv, 0, kHeadDim, wave, lane, 0, none);
-  src_q.issue(0, kHeadDim, q_tile, wave, ld_qkv, none);
-  src_k.issue(0, kHeadDim, k_tile, wave, ld_qkv, none);
-  src_v.issue(0, seq, v_tile, wave, ld_qkv, none);
-  src_v.issue(1, seq, v_tile + kHeadDim * kRowBytes, wave, ld_qkv, none);
-  wait_loads_and_barrier<0>();
-
-  // scores of this wave's 32 queries against all keys
-  f32x16 s[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[j][r] = 0.f;
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const u32x4 a = read_fragment<kSeqMax, Layout::RowK>(q_tile, 32 * wave, g, lane);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const u32x4 kb = read_fragment<kSeqMax, Layout::RowK>(k_tile, 32 * j, g, lane);
-      s[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, kb), s[j], 0, 0, 0);
-    }
-  }
-  // softmax over the keys of each row: accumulator register r of tile j holds (row 8 (r / 4) + 4 (lane / 32) + r % 4,
-  // key 32 j + lane % 32), so a row is spread over the 32 lanes of a half-wave
-  const int key0 = lane & 31;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    float m = -INFINITY;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      s[j][r] = 32 * j + key0 < seq ? s[j][r] * scale : -INFINITY;
-      m = fmaxf(m, s[j][r]);
-    }
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-    float sum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) { s[j][r] = __expf(s[j][r] - m); sum += s[j][r]; }   // the hardware exponential: P is rounded to bfloat16 next
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-    const float inv = 1.f / sum;
-    const int row = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int key = 32 * j + key0;                    // k tile key / 64, chunk (key % 64) / 8, element key % 8
-      bf16_t v;
-      store_elem(&v, s[j][r] * inv);
-      *reinterpret_cast<bf16_t*>(p_tile + (key >> 6) * (32 * kRowBytes) + lds_offset(row, (key & 63) >> 3) + (key & 7) * 2) = v;
-    }
-  }
-  asm volatile("" ::: "memory");  // the parked P is read back through pointers of another type
-  // ctx = P V with the parked bfloat16 P as A and the transposing reads of V as B
-  f32x16 o[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
-#pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      u32x4 a[1], vb[2];
-      a[0] = read_fragment<32, Layout::RowK>(p_tile + kt * (32 * kRowBytes), 0, g, lane);
-      vb[0] = read_fragment<kHeadDim, Layout::KRow>(v_tile + kt * (kHeadDim * kRowBytes), 0, g, lane);
-      vb[1] = read_fragment<kHeadDim, Layout::KRow>(v_tile + kt * (kHeadDim * kRowBytes), 32, g, lane);
-      fragments_ready(a, vb);
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        o[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[0]), __builtin_bit_cast(bf16x8, vb[j]), o[j], 0, 0, 0);
-    }
-  }
-  // P to HBM (only when it is kept): 16-byte chunks from the parked tiles; LDS operations of a wave run in order
-  const int q0 = 32 * wave;
-  if (prob) {
-    bf16_t* dst = prob + (size_t)z * seq * seq;
-#pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int idx = it * 64 + lane, row = idx >> 4, chunk = idx & 15;   // 32 rows x 16 chunks of 8 keys
-      if (q0 + row < seq && chunk * 8 < seq) {
-        const u32x4 v = *reinterpret_cast<const u32x4*>(p_tile + (chunk >> 3) * (32 * kRowBytes) + lds_offset(row, chunk & 7));
-        *reinterpret_cast<u32x4*>(dst + (size_t)(q0 + row) * seq + chunk * 8) = v;
-      }
-    }
-  }
-  asm volatile("" ::: "memory");
-  // ctx through the same LDS region (P is dead once its fragments and its copy are read): 32 rows x 64 floats
-  float* stage = reinterpret_cast<float*>(p_tile);
-  constexpr int kPitch = kHeadDim;  // no padding: the region is exactly 32 x 64 floats
-  static_assert(32 * kPitch * 4 <= kPWave, "ctx staging fits in the wave's P region");
-#pragma unroll
-  for (int j = 0; j < 2; ++j)
-#pragma unroll
-    for (int r = 0; r < 16; ++r)
-      stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * kPitch + 32 * j + (lane & 31)] = o[j][r];
-  asm volatile("" ::: "memory");
-  bf16_t* out = ctx + (size_t)b * seq * ld_ctx + h * kHeadDim;
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = it * 8 + (lane >> 3), c = (lane & 7) * 8;
-    if (q0 + row < seq) {
-      float v[8];
-      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c), v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + c + 4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
-      *reinterpret_cast<u32x4*>(out + (size_t)(q0 + row) * ld_ctx + c) = pack_bf16x8(v);
-    }
-  }
-}
-
-
-// Backward of the same attention, one workgroup per (batch entry, head):
-//   dP = dctx V^T;  dS = P * (dP - rowsum(dP * P)) * scale (rounded to bfloat16, as the unfused path stores it);
-//   dQ = dS K;  dK = dS^T Q;  dV = P^T dctx.
-// Phase 1 is row-wise: wave w forms dP and dS of its 32 queries in the accumulators (P comes straight from HBM in
-// that layout) and writes dS once, into a workgroup-wide KRow tile (k = query) that dK reads; its own dQ product
-// takes dS from the registers.  After one barrier, phase 2: wave w produces rows 32 w .. of dQ, dK and dV, three
-// products of 16 MFMAs each, with K, Q and dctx read through transposing LDS reads and P as a KRow tile that came
-// in by direct-to-LDS loads.  LDS: dctx twice (RowK for dP, KRow for dV), V (RowK), K, Q (KRow), P (KRow), the KRow dS
-// tile, which takes over the space of dctx-RowK and V once dP is done, and 8 KB per wave through which results leave.
-constexpr int kDsK = kSeqMax * 2 * kSeqMax;  // dS as KRow tiles: two k tiles of 64 queries x 128 key rows
-constexpr int kBwdLds = kQBytes /*dctx RowK*/ + kQBytes /*V RowK*/ + 3 * kVBytes /*dctx, K, Q as KRow*/ + kDsK /*P KRow*/ + 4 * kPWave;
-static_assert(2 * kQBytes == kDsK, "the KRow dS tile reuses the dctx and V tiles of phase 1");
 
 // Rotation of the KRow dS tile (see the kernel): by 2 chunks per k-row, modulo 8 k-rows.
 __device__ __forceinline__ int dsk_rot(int k) { return (k & 7) << 1; }
@@ -186,6 +46,158 @@ __device__ __forceinline__ u32x4 read_krow(const char* tile, int frag_row0, int 
   }
   return out;
 }
+
+__global__ __launch_bounds__(256) void attention_fwd_kernel(const bf16_t* __restrict__ qkv, int ld_qkv, bf16_t* __restrict__ prob,
+                                                            bf16_t* __restrict__ ctx, int ld_ctx, int heads, int seq, float scale) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  char* q_tile = lds;
+  char* k_tile = lds + kQBytes;
+  char* v_tile = lds + 2 * kQBytes;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  char* p_tile = lds + 2 * kQBytes + kVBytes + wave * kPWave;
+  const int z = blockIdx.x, b = z / heads, h = z - b * heads;
+  const int hidden = heads * kHeadDim;
+  const bf16_t* base = qkv + (size_t)b * seq * ld_qkv + h * kHeadDim;
+  ConvGeom none{};
+
+  TileSource<kSeqMax, Layout::RowK, Gather::None, 4> src_q, src_k;
+  TileSource<kHeadDim, Layout::KRow, Gather::None, 4> src_v;
+  src_q.init(base, ld_qkv, 0, seq, wave, lane, 0, none);
+  src_k.init(base + hidden, ld_qkv, 0, seq, wave, lane, 0, none);
+  src_v.init(base + 2 * hidden, ld_qkv, 0, kHeadDim, wave, lane, 0, none);
+  src_q.issue(0, kHeadDim, q_tile, wave, ld_qkv, none);
+  src_k.issue(0, kHeadDim, k_tile, wave, ld_qkv, none);
+  src_v.issue(0, seq, v_tile, wave, ld_qkv, none);
+  src_v.issue(1, seq, v_tile + kHeadDim * kRowBytes, wave, ld_qkv, none);
+  wait_loads_and_barrier<0>();
+
+  // Scores of this wave's 32 queries against all keys, multiplied with the MFMA operands exchanged: lane l holds, of
+  // query q0 + l % 32, the keys 32 j + 8 (r / 4) + 4 (l / 32) + r % 4 of key block j.  A row of the softmax then lies
+  // in two lanes (maximum and sum are 63 in-lane operations and one exchange), four consecutive registers are four
+  // consecutive keys (P parks in LDS with 8-byte writes) and eight consecutive registers are, up to the order of k,
+  // an A fragment of ctx = P V, which therefore comes straight from the registers.
+  const int q0 = 32 * wave, qi = lane & 31, hh = lane >> 5;
+  f32x16 s[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[j][r] = 0.f;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const u32x4 a = read_fragment<kSeqMax, Layout::RowK>(q_tile, q0, g, lane);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const u32x4 kb = read_fragment<kSeqMax, Layout::RowK>(k_tile, 32 * j, g, lane);
+      s[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kb), __builtin_bit_cast(bf16x8, a), s[j], 0, 0, 0);
+    }
+  }
+  float m = -INFINITY;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      s[j][r] = 32 * j + 8 * (r >> 2) + 4 * hh + (r & 3) < seq ? s[j][r] * scale : -INFINITY;
+      m = fmaxf(m, s[j][r]);
+    }
+  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  float sum = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[j][r] = __expf(s[j][r] - m); sum += s[j][r]; }   // the hardware exponential: P is rounded to bfloat16 next
+  sum += __shfl_xor(sum, 32, 64);
+  const float inv = 1.f / sum;
+  // P, rounded to bfloat16 and packed two keys to a word: pp[j][4 g + e] holds keys 32 j + 8 g + 4 hh + 2 e, + 1
+  uint32_t pp[4][8];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pp[j][e] = pack_bf16(s[j][2 * e] * inv, s[j][2 * e + 1] * inv);
+  // ctx = P V: the A fragment of k-group g of key tile kt is pp[2 kt + g / 2][4 (g % 2) ..]; V's fragments are
+  // fetched in the same order of k (see read_krow)
+  f32x16 o[2];
+#pragma unroll
+  for (int n = 0; n < 2; ++n)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[n][r] = 0.f;
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      u32x4 a[1], vb[2];
+      const int j = 2 * kt + (g >> 1), e0 = 4 * (g & 1);
+      a[0] = u32x4{pp[j][e0], pp[j][e0 + 1], pp[j][e0 + 2], pp[j][e0 + 3]};
+      vb[0] = read_krow<kHeadDim, false, true>(v_tile + kt * (kHeadDim * kRowBytes), 0, g, lane);
+      vb[1] = read_krow<kHeadDim, false, true>(v_tile + kt * (kHeadDim * kRowBytes), 32, g, lane);
+      fragments_ready(a, vb);
+#pragma unroll
+      for (int n = 0; n < 2; ++n)
+        o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vb[n]), __builtin_bit_cast(bf16x8, a[0]), o[n], 0, 0, 0);
+    }
+  }
+  // P to HBM (only when it is kept): parked per wave as RowK tiles (two k tiles of 64 keys x 32 query rows) with
+  // 8-byte writes, read back as 16-byte chunks so that whole rows leave; LDS operations of a wave run in order
+  if (prob) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int key = 32 * j + 8 * g + 4 * hh;
+        *reinterpret_cast<uint2*>(p_tile + (key >> 6) * (32 * kRowBytes) + lds_offset(qi, (key & 63) >> 3) + (key & 7) * 2) = uint2{pp[j][2 * g], pp[j][2 * g + 1]};
+      }
+    asm volatile("" ::: "memory");  // read back through pointers of another type
+    bf16_t* dst = prob + (size_t)z * seq * seq;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int idx = it * 64 + lane, row = idx >> 4, chunk = idx & 15;   // 32 rows x 16 chunks of 8 keys
+      if (q0 + row < seq && chunk * 8 < seq) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(p_tile + (chunk >> 3) * (32 * kRowBytes) + lds_offset(row, chunk & 7));
+        *reinterpret_cast<u32x4*>(dst + (size_t)(q0 + row) * seq + chunk * 8) = v;
+      }
+    }
+  }
+  asm volatile("" ::: "memory");
+  // ctx through the same LDS region (P is dead once its copy is read): 32 rows x 64 floats, four consecutive
+  // features per 16-byte write, the 16 chunks of a row permuted by row % 16 (see the backward kernel's write_out)
+  float* stage = reinterpret_cast<float*>(p_tile);
+  constexpr int kPitch = kHeadDim;  // no padding: the region is exactly 32 x 64 floats
+  static_assert(32 * kPitch * 4 <= kPWave, "ctx staging fits in the wave's P region");
+#pragma unroll
+  for (int n = 0; n < 2; ++n)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int chunk = (8 * n + 2 * g + hh) ^ (qi & 15);
+      *reinterpret_cast<f32x4*>(stage + qi * kPitch + chunk * 4) = f32x4{o[n][4 * g], o[n][4 * g + 1], o[n][4 * g + 2], o[n][4 * g + 3]};
+    }
+  asm volatile("" ::: "memory");
+  bf16_t* out = ctx + (size_t)b * seq * ld_ctx + h * kHeadDim;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int row = it * 8 + (lane >> 3), c = (lane & 7) * 2;
+    if (q0 + row < seq) {
+      float v[8];
+      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + (c ^ (row & 15)) * 4);
+      const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + row * kPitch + ((c + 1) ^ (row & 15)) * 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = v0[e]; v[4 + e] = v1[e]; }
+      *reinterpret_cast<u32x4*>(out + (size_t)(q0 + row) * ld_ctx + c * 4) = pack_bf16x8(v);
+    }
+  }
+}
+
+// Backward of the same attention, one workgroup per (batch entry, head):
+//   dP = dctx V^T;  dS = P * (dP - rowsum(dP * P)) * scale (rounded to bfloat16, as the unfused path stores it);
+//   dQ = dS K;  dK = dS^T Q;  dV = P^T dctx.
+// Phase 1 is row-wise: wave w forms dP and dS of its 32 queries in the accumulators (P comes straight from HBM in
+// that layout) and writes dS once, into a workgroup-wide KRow tile (k = query) that dK reads; its own dQ product
+// takes dS from the registers.  After one barrier, phase 2: wave w produces rows 32 w .. of dQ, dK and dV, three
+// products of 16 MFMAs each, with K, Q and dctx read through transposing LDS reads and P as a KRow tile that came
+// in by direct-to-LDS loads.  LDS: dctx twice (RowK for dP, KRow for dV), V (RowK), K, Q (KRow), P (KRow), the KRow dS
+// tile, which takes over the space of dctx-RowK and V once dP is done, and 8 KB per wave through which results leave.
+constexpr int kDsK = kSeqMax * 2 * kSeqMax;  // dS as KRow tiles: two k tiles of 64 queries x 128 key rows
+constexpr int kBwdLds = kQBytes /*dctx RowK*/ + kQBytes /*V RowK*/ + 3 * kVBytes /*dctx, K, Q as KRow*/ + kDsK /*P KRow*/ + 4 * kPWave;
+static_assert(2 * kQBytes == kDsK, "the KRow dS tile reuses the dctx and V tiles of phase 1");
 
 __global__ __launch_bounds__(256) void attention_bwd_kernel(const bf16_t* __restrict__ qkv, int ld_qkv, const bf16_t* __restrict__ prob,
                                                             const bf16_t* __restrict__ dctx, int ld_ctx, bf16_t* __restrict__ dqkv,
