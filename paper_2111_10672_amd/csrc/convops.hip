@@ -110,9 +110,9 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
 
 // out_a[c] = sum_b partial[b][0][c], out_b[c] = sum_b partial[b][1][c].  One wavefront per column: lane l adds blocks
 // l, l + 64, ... in order, then the 64 lane sums are combined by a fixed shuffle tree (same bits on every run).
-__global__ __launch_bounds__(256) void reduce_pairs_kernel(const float* __restrict__ partial, int n_blocks, int width,
-                                                           float* __restrict__ out_a, float* __restrict__ out_b) {
-  const int lane = threadIdx.x & 63, col = blockIdx.x * 4 + (threadIdx.x >> 6);
+__device__ __forceinline__ void reduce_pairs_block(unsigned block, const float* __restrict__ partial, int n_blocks, int width,
+                                                   float* __restrict__ out_a, float* __restrict__ out_b) {
+  const int lane = threadIdx.x & 63, col = block * 4 + (threadIdx.x >> 6);
   if (col >= 2 * width) return;
   float s = 0.f;
   for (int b = lane; b < n_blocks; b += 64) s += partial[(size_t)b * 2 * width + col];
@@ -123,24 +123,32 @@ __global__ __launch_bounds__(256) void reduce_pairs_kernel(const float* __restri
     else out_b[col - width] = s;
   }
 }
+__global__ __launch_bounds__(256) void reduce_pairs_kernel(const float* __restrict__ partial, int n_blocks, int width,
+                                                           float* __restrict__ out_a, float* __restrict__ out_b) {
+  reduce_pairs_block(blockIdx.x, partial, n_blocks, width, out_a, out_b);
+}
 
 // out[j] = sum over slices of partial[slice][map(j)], slices added in index order; map drops padded input channels.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices, long long slice_stride,
-                                                            float* __restrict__ out, long long numel, int cin, int cin_padded) {
-  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void splitk_reduce_block(unsigned block, const float* __restrict__ partial, int slices, long long slice_stride,
+                                                    float* __restrict__ out, long long numel, int cin, int cin_padded) {
+  const long long j = (long long)block * 256 + threadIdx.x;
   if (j >= numel) return;
   const long long src = cin == cin_padded ? j : (j / cin) * cin_padded + (j % cin);
   float s = 0.f;
   for (int z = 0; z < slices; ++z) s += partial[(size_t)z * slice_stride + src];
   out[j] = s;
 }
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int slices, long long slice_stride,
+                                                            float* __restrict__ out, long long numel, int cin, int cin_padded) {
+  splitk_reduce_block(blockIdx.x, partial, slices, slice_stride, out, numel, cin, cin_padded);
+}
 
 // The same for tensors without channel padding, four neighbouring elements per thread and four slices requested
 // at a time (the additions still run in slice order).
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const f32x4* __restrict__ partial, int slices, long long slice_stride4,
-                                                             f32x4* __restrict__ out, long long numel4) {
-  const long long j = (long long)blockIdx.x * 256 + threadIdx.x;
+__device__ __forceinline__ void splitk_reduce4_block(unsigned block, const f32x4* __restrict__ partial, int slices, long long slice_stride4,
+                                                     f32x4* __restrict__ out, long long numel4) {
+  const long long j = (long long)block * 256 + threadIdx.x;
   if (j >= numel4) return;
   f32x4 s = {0.f, 0.f, 0.f, 0.f};
   int z = 0;
@@ -151,6 +159,24 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const f32x4* __rest
   }
   for (; z < slices; ++z) s += partial[(size_t)z * slice_stride4 + j];
   out[j] = s;
+}
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const f32x4* __restrict__ partial, int slices, long long slice_stride4,
+                                                             f32x4* __restrict__ out, long long numel4) {
+  splitk_reduce4_block(blockIdx.x, partial, slices, slice_stride4, out, numel4);
+}
+
+// Several of the reductions above in one launch: the column sums of a unit's affine backward passes and the k-slice
+// sums of its weight gradients are a handful of tiny kernels each bound by its launch; a table in the kernel
+// arguments says which range of workgroups does which, with the arithmetic (and so the bits) of the kernels above.
+__global__ __launch_bounds__(256) void unit_reduce_kernel(ReduceTable t) {
+  int i = 0;
+  while (i + 1 < t.n && blockIdx.x >= t.end_block[i]) ++i;
+  const unsigned block = blockIdx.x - (i ? t.end_block[i - 1] : 0u);
+  const ReduceTask& k = t.task[i];
+  if (k.kind == ReduceTask::kPairs) reduce_pairs_block(block, k.partial, k.count, k.width, k.out, k.out_b);
+  else if (k.kind == ReduceTask::kSlices4)
+    splitk_reduce4_block(block, reinterpret_cast<const f32x4*>(k.partial), k.count, k.stride, reinterpret_cast<f32x4*>(k.out), k.numel);
+  else splitk_reduce_block(block, k.partial, k.count, k.stride, k.out, k.numel, k.cin, k.cin_padded);
 }
 
 // The same with a bfloat16 result (the input gradient of a product whose k range was cut into slices): eight
@@ -302,7 +328,7 @@ size_t affine_partial_floats(long long rows, int channels) {
 }
 
 hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void* y, const void* scale, void* dy, void* dsum,
-                                  float* partial, float* dscale, float* dshift, long long rows, int channels, hipStream_t s) {
+                                  float* partial, float* dscale, float* dshift, long long rows, int channels, hipStream_t s, ReduceTask* deferred) {
   if (!dout || !y || !scale || !dy || !partial || !dscale || !dshift || rows <= 0 || channels <= 0 || channels % 8 || channels > 2048)
     return hipErrorInvalidValue;
   const int rpb = affine_rows_per_block(rows, channels);
@@ -313,8 +339,46 @@ hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void*
                      (const uint16_t*)y, (const uint16_t*)scale, (uint16_t*)dy, (uint16_t*)dsum, partial, rows, channels, rpb);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (deferred) {   // the caller adds the column sums up later (launch_unit_reduce)
+    deferred->kind = ReduceTask::kPairs; deferred->partial = partial; deferred->count = blocks; deferred->width = channels;
+    deferred->out = dscale; deferred->out_b = dshift; deferred->blocks = (unsigned)((2 * channels + 3) / 4);
+    return hipSuccess;
+  }
   hipLaunchKernelGGL(reduce_pairs_kernel, dim3((2 * channels + 3) / 4), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
   return hipGetLastError();
+}
+
+bool make_splitk_reduce_task(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,
+                             ReduceTask* task) {
+  if (!partial || !out || !task || slices < 1 || numel <= 0 || cin <= 0 || cin_padded < cin) return false;
+  task->partial = partial; task->count = slices; task->out = out; task->out_b = nullptr; task->width = 0;
+  task->cin = cin; task->cin_padded = cin_padded;
+  if (cin == cin_padded && numel % 4 == 0 && slice_stride % 4 == 0 && (reinterpret_cast<uintptr_t>(partial) & 15) == 0 &&
+      (reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+    task->kind = ReduceTask::kSlices4; task->stride = slice_stride / 4; task->numel = numel / 4;
+  } else {
+    task->kind = ReduceTask::kSlices; task->stride = slice_stride; task->numel = numel;
+  }
+  task->blocks = blocks_for(task->numel);
+  return true;
+}
+
+hipError_t launch_unit_reduce(const ReduceTask* tasks, int n, hipStream_t s) {
+  if (!tasks || n < 1) return hipErrorInvalidValue;
+  for (int first = 0; first < n; first += ReduceTable::kMax) {   // more than a table holds: several launches
+    ReduceTable t;
+    t.n = std::min(n - first, (int)ReduceTable::kMax);
+    unsigned end = 0;
+    for (int i = 0; i < t.n; ++i) {
+      t.task[i] = tasks[first + i];
+      if (t.task[i].blocks == 0) return hipErrorInvalidValue;
+      end += t.task[i].blocks;
+      t.end_block[i] = end;
+    }
+    hipLaunchKernelGGL(unit_reduce_kernel, dim3(end), dim3(256), 0, s, t);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 hipError_t launch_splitk_reduce(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,

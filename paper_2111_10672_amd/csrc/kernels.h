@@ -134,9 +134,37 @@ hipError_t launch_fill_zero(void* ptr, size_t bytes, hipStream_t stream);
 // Backward of "per-channel affine, then optional ReLU whose output is act": dz = dout * [act > 0] (dz = dout if act is
 // null); dy = scale * dz; dsum = dz (optional); dscale[c] = sum dz * y; dshift[c] = sum dz (float32, overwritten).
 // partial: scratch of affine_partial_floats(rows, channels) floats.
+// With `deferred` the column sums stay per-workgroup partial sums and *deferred describes the reduction that finishes
+// them (for launch_unit_reduce); dscale and dshift are written by that reduction.
 size_t affine_partial_floats(long long rows, int channels);
+// One small fixed-order reduction: kPairs = the column sums of an affine backward pass (partial [count][2][width] ->
+// out [width], out_b [width]); kSlices / kSlices4 = the k-slices of a weight gradient (see launch_splitk_reduce;
+// kSlices4 counts in groups of four floats).  blocks = workgroups it takes.
+struct ReduceTask {
+  enum Kind { kPairs = 0, kSlices4 = 1, kSlices = 2 };
+  int kind = kPairs;
+  const float* partial = nullptr;
+  int count = 0, width = 0;
+  long long stride = 0, numel = 0;
+  float* out = nullptr;
+  float* out_b = nullptr;
+  int cin = 0, cin_padded = 0;
+  unsigned blocks = 0;
+};
+struct ReduceTable {
+  static constexpr int kMax = 8;
+  int n = 0;
+  unsigned end_block[kMax] = {};
+  ReduceTask task[kMax];
+};
 hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void* y, const void* scale, void* dy, void* dsum,
-                                  float* partial, float* dscale, float* dshift, long long rows, int channels, hipStream_t s);
+                                  float* partial, float* dscale, float* dshift, long long rows, int channels, hipStream_t s,
+                                  ReduceTask* deferred = nullptr);
+// The reduction launch_splitk_reduce would run, as a task; false if the arguments are not valid.
+bool make_splitk_reduce_task(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,
+                             ReduceTask* task);
+// All of the tasks in one launch (several if there are more than ReduceTable::kMax), same bits as one launch each.
+hipError_t launch_unit_reduce(const ReduceTask* tasks, int n, hipStream_t s);
 // out[j] = sum over slices of partial[slice * slice_stride + map(j)], j < numel; map(j) = j, or with cin < cin_padded
 // (j / cin) * cin_padded + j % cin (drops the zero channels a 3-channel input was padded with).
 hipError_t launch_splitk_reduce(const float* partial, int slices, long long slice_stride, float* out, long long numel, int cin, int cin_padded,

@@ -119,7 +119,8 @@ class ResnetModel : public Model {
     std::vector<UnitBuf> unit;   // stem, blocks
     size_t pooled, logits, row_loss, dlogits, dpooled;
     size_t g[8];                 // backward transients: gradients of activations
-    size_t affine_partial, wgrad_partial;
+    static constexpr int kReduceSlots = 4;   // a unit has at most three convolutions and a projection
+    size_t affine_partial[kReduceSlots], wgrad_partial[kReduceSlots];
     size_t total;
   };
   static constexpr int kFwdPool = 8;
@@ -195,7 +196,7 @@ class ResnetModel : public Model {
     p.dlogits = take((size_t)batch_ * align_up((size_t)classes_, 8) * 2);
     p.dpooled = take((size_t)batch_ * features_ * 2);
     for (auto& g : p.g) g = 0;
-    p.affine_partial = p.wgrad_partial = 0;
+    for (int j = 0; j < Plan::kReduceSlots; ++j) p.affine_partial[j] = p.wgrad_partial[j] = 0;
     if (k >= 2) {
       for (auto& g : p.g) g = take(amax);
       size_t ap = 0, wp = 0;
@@ -205,8 +206,8 @@ class ResnetModel : public Model {
       };
       see(stem_);
       for (const Block& b : blocks_) { for (const Conv& c : b.convs) see(c); if (b.has_proj) see(b.proj); }
-      p.affine_partial = take(ap);
-      p.wgrad_partial = take(wp);
+      // one buffer of each kind per convolution of a unit: their reductions wait for the unit's end (see backward)
+      for (int j = 0; j < Plan::kReduceSlots; ++j) { p.affine_partial[j] = take(ap); p.wgrad_partial[j] = take(wp); }
     }
     p.total = off;
     return p;
@@ -266,15 +267,31 @@ class ResnetModel : public Model {
     g.name = "conv_wgrad";
     if (int rc = gemm(g, s)) return rc;
     const long long numel = (long long)c.cout * c.k * c.k * c.cin;
-    return run("splitk_reduce", (double)(g.k_splits + 1) * numel * 4, s, [&] {
-      return launch_splitk_reduce(partial, g.k_splits, (long long)c.cout * g.N, dw, numel, c.cin, c.cin_eff, s); });
+    ReduceTask task;   // the k-slices are added up with the unit's other small reductions
+    if (!make_splitk_reduce_task(partial, g.k_splits, (long long)c.cout * g.N, dw, numel, c.cin, c.cin_eff, &task)) return check(hipErrorInvalidValue, "weight-gradient reduction");
+    reduce_bytes_ += (double)(g.k_splits + 1) * numel * 4;
+    reduces_.push_back(task);
+    return SPB_OK;
   }
   // gradient at the affine's output -> dy, dscale, dshift (and the masked gradient itself, if asked for)
   int affine_bwd(const Conv& c, const void* dout, const void* act, const void* y, void* dy, void* dsum, float* partial, hipStream_t s) {
     const long long rows = c.out_rows(batch_);
-    return run("affine_relu_bwd", (double)rows * c.cout * 2 * (3 + (act ? 1 : 0) + (dsum ? 1 : 0)), s, [&] {
-      return launch_affine_relu_bwd(dout, act, y, param_ptrs[c.scale], dy, dsum, partial, static_cast<float*>(grad_ptrs[c.scale]),
-                                    static_cast<float*>(grad_ptrs[c.shift]), rows, c.cout, s); });
+    ReduceTask task;
+    if (int rc = run("affine_relu_bwd", (double)rows * c.cout * 2 * (3 + (act ? 1 : 0) + (dsum ? 1 : 0)), s, [&] {
+          return launch_affine_relu_bwd(dout, act, y, param_ptrs[c.scale], dy, dsum, partial, static_cast<float*>(grad_ptrs[c.scale]),
+                                        static_cast<float*>(grad_ptrs[c.shift]), rows, c.cout, s, &task); })) return rc;
+    reduce_bytes_ += (double)task.count * 2 * c.cout * 4;
+    reduces_.push_back(task);
+    return SPB_OK;
+  }
+  // The small reductions a unit's backward pass has collected (column sums of its affine passes, k-slices of its
+  // weight gradients), in one launch.  They finish parameter gradients only, so they go where weight gradients go.
+  int flush_reduces(hipStream_t to) {
+    if (reduces_.empty()) return SPB_OK;
+    const int rc = run("unit_reduce", reduce_bytes_, to, [&] { return launch_unit_reduce(reduces_.data(), (int)reduces_.size(), to); });
+    reduces_.clear();
+    reduce_bytes_ = 0.0;
+    return rc;
   }
 
   int forward(const void* x, const int32_t* labels, const int32_t*, int k, void* wsp, float* loss_out, hipStream_t s) override {
@@ -341,8 +358,12 @@ class ResnetModel : public Model {
     char* w = static_cast<char*>(ws);
     const int cut = num_units - k;
     const int lddz = (int)align_up((size_t)classes_, 8), hw = final_h_ * final_w_;
-    float* apart = reinterpret_cast<float*>(w + p.affine_partial);
-    float* wpart = reinterpret_cast<float*>(w + p.wgrad_partial);
+    // partial-sum buffers of a unit's convolutions: slot j for convolution j, the last slot for the projection
+    auto apart = [&](int j) { return reinterpret_cast<float*>(w + p.affine_partial[j]); };
+    auto wpart = [&](int j) { return reinterpret_cast<float*>(w + p.wgrad_partial[j]); };
+    constexpr int kProjSlot = Plan::kReduceSlots - 1;
+    reduces_.clear();
+    reduce_bytes_ = 0.0;
     // ---- head ----
     {
       GemmProblem g;  // dW = dlogits^T pooled; db = column sums
@@ -379,26 +400,34 @@ class ResnetModel : public Model {
       int reader[2] = {-1, -1};   // mark of the weight-gradient product that last read slot 3 / slot 5
       int dy_slot = 0;            // dy lives in slot 3 + 2 * dy_slot
       // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut
-      if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart, s)) return rc;
+      if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart(last), s)) return rc;
       for (int j = last; j >= 1; --j) {
         const void* in_j = w + u.conv[j - 1].a;
-        if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[j].w]), fork(s))) return rc;
+        if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart(j), static_cast<float*>(grad_ptrs[b.convs[j].w]), fork(s))) return rc;
         reader[dy_slot] = mark();
         if (int rc = conv_dgrad(b.convs[j], dy, param_ptrs[b.convs[j].w], nullptr, da, s)) return rc;
         const int next_slot = dy_slot ^ 1;
         void* dy_next = w + p.g[3 + 2 * next_slot];
         if (int rc = wait_mark(s, reader[next_slot])) return rc;   // whoever read that slot is done with it
         reader[next_slot] = -1;
-        if (int rc = affine_bwd(b.convs[j - 1], da, in_j, w + u.conv[j - 1].y, dy_next, nullptr, apart, s)) return rc;
+        if (int rc = affine_bwd(b.convs[j - 1], da, in_j, w + u.conv[j - 1].y, dy_next, nullptr, apart(j - 1), s)) return rc;
         dy = dy_next;
         dy_slot = next_slot;
       }
-      if (int rc = conv_wgrad(b.convs[0], x_in, dy, wpart, static_cast<float*>(grad_ptrs[b.convs[0].w]), fork(s))) return rc;
       const void* shortcut_grad = dsum;
+      void* dys = w + p.g[6];
+      if (b.has_proj)
+        if (int rc = affine_bwd(b.proj, dsum, nullptr, w + u.proj.y, dys, nullptr, apart(kProjSlot), s)) return rc;
+      {
+        // the unit's last weight gradients and, behind them, all of its small reductions: the fork comes after every
+        // affine pass of the unit, and nothing below reads what the reductions write
+        hipStream_t side = fork(s);
+        if (int rc = conv_wgrad(b.convs[0], x_in, dy, wpart(0), static_cast<float*>(grad_ptrs[b.convs[0].w]), side)) return rc;
+        if (b.has_proj)
+          if (int rc = conv_wgrad(b.proj, x_in, dys, wpart(kProjSlot), static_cast<float*>(grad_ptrs[b.proj.w]), side)) return rc;
+        if (int rc = flush_reduces(side)) return rc;
+      }
       if (b.has_proj) {
-        void* dys = w + p.g[6];
-        if (int rc = affine_bwd(b.proj, dsum, nullptr, w + u.proj.y, dys, nullptr, apart, s)) return rc;
-        if (int rc = conv_wgrad(b.proj, x_in, dys, wpart, static_cast<float*>(grad_ptrs[b.proj.w]), fork(s))) return rc;
         if (need_dx) {
           if (int rc = conv_dgrad(b.proj, dys, param_ptrs[b.proj.w], nullptr, w + p.g[7], s)) return rc;
           shortcut_grad = w + p.g[7];
@@ -420,9 +449,10 @@ class ResnetModel : public Model {
               return launch_maxpool_bwd(dout, reinterpret_cast<const uint8_t*>(w + su.which), w + p.g[4], batch_, stem_.out_h, stem_.out_w, stem_.cout, s); })) return rc;
         d = w + p.g[4];
       }
-      if (int rc = affine_bwd(stem_, d, w + su.conv[0].a, w + su.conv[0].y, w + p.g[3], nullptr, apart, s)) return rc;
+      if (int rc = affine_bwd(stem_, d, w + su.conv[0].a, w + su.conv[0].y, w + p.g[3], nullptr, apart(0), s)) return rc;
       const void* stem_in = stem_.cin_eff != stem_.cin ? (const void*)(w + su.xpad) : x_;
-      if (int rc = conv_wgrad(stem_, stem_in, w + p.g[3], wpart, static_cast<float*>(grad_ptrs[stem_.w]), s)) return rc;
+      if (int rc = conv_wgrad(stem_, stem_in, w + p.g[3], wpart(0), static_cast<float*>(grad_ptrs[stem_.w]), s)) return rc;
+      if (int rc = flush_reduces(s)) return rc;
     }
     return SPB_OK;
   }
@@ -458,6 +488,8 @@ class ResnetModel : public Model {
   std::vector<Block> blocks_;
   int fc_w_ = -1, fc_b_ = -1;
   const void* x_ = nullptr;
+  std::vector<ReduceTask> reduces_;   // of the unit whose backward pass is being enqueued
+  double reduce_bytes_ = 0.0;
 };
 
 }  // namespace
