@@ -320,6 +320,7 @@ hipError_t launch_gemm(const GemmProblem& p, hipStream_t stream) {
   if (p.dtype == DType::F32 && gemm_f32_small_accepts(p)) return launch_gemm_f32_small(p, stream);
   // the register-staged kernel below knows only the dense-layer epilogues of a single product
   if (p.batch != 1 || p.alpha != 1.f || p.residual || p.aux_out || p.act == Act::Gelu || p.epilogue == Epilogue::ScaleStore ||
+      p.epilogue == Epilogue::AffineBwdStore ||
       p.col_scale || p.a_gather != Gather::None || p.b_gather != Gather::None || p.k_splits != 1)
     return hipErrorInvalidValue;
   if (p.dtype == DType::F32) return launch_typed<float>(p, stream);

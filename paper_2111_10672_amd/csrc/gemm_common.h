@@ -48,6 +48,7 @@ struct GemmParams {
   const void* A; const void* B; void* C;
   const void* bias; const void* mask; float* a_row_sum;
   const void* residual; void* aux_out; const void* col_scale;
+  const void* affine_y; float* col_partial; int ldy;
   int M, N, K, lda, ldb, ldc, ldmask, ldres, ldaux;
   int epilogue, act, aux_raw, aux_act_grad;
   float alpha;
@@ -130,6 +131,8 @@ inline GemmParams make_params(const GemmProblem& q, int bm, int bn) {
   p.epilogue = (int)q.epilogue; p.act = q.relu ? (int)Act::Relu : (int)q.act;
   p.alpha = q.alpha; p.col_scale = q.col_scale; p.aux_raw = q.aux_raw; p.aux_act_grad = q.aux_act_grad;
   p.conv = q.conv;
+  p.affine_y = q.affine_y; p.ldy = q.ldaffine_y; p.col_partial = q.col_partial;
+  if (q.col_partial_rows) *q.col_partial_rows = (q.M + bm - 1) / bm;
   p.k_tiles_per_split = 0;
   p.a_batch = q.a_batch; p.b_batch = q.b_batch; p.c_batch = q.c_batch;
   p.tiles_m = (q.M + bm - 1) / bm;

@@ -582,8 +582,11 @@ __device__ __forceinline__ void store_rows_bf16(const GemmParams& p, const float
 // it, a lane's column and its per-column operands never change, a row's address is the previous one plus a constant,
 // and the per-element chunks of the next 32 rows are requested before the current ones are stored, so waiting for
 // them never waits for a store.  The arithmetic per element is that of store_rows_bf16.
-template <int WM, int WN>
-__device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage, int row_base, int col_base, int lane, long long c_offset) {
+// wm, tile_m: the wave's place among the WAVES_M waves that share its columns and the tile's row of tiles (the fused
+// affine backward adds its column sums up over those waves and files them under that row).
+template <int WM, int WN, int WAVES_M>
+__device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&acc)[WM / 32][WN / 32], float* stage, int row_base, int col_base, int lane, long long c_offset,
+                                                int wm, int tile_m) {
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int kPitch = WN + 4;  // floats; the 16-byte pad staggers the banks of consecutive rows
   float* park_at = stage + (lane & 31) * kPitch + 4 * (lane >> 5);
@@ -615,12 +618,8 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
         const int row = row0 + it * kRowStep, m = row_base + i * 32 + row;
         if (row >= 32 || m >= p.M) break;
         const f32x4 v = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch);
-        if (whole) {
-          *reinterpret_cast<f32x4*>(to + (size_t)it * kRowStep * p.ldc) = v * p.alpha + b;
-        } else {
-          float t[4] = {v[0], v[1], v[2], v[3]};
-          store_ragged(p, t, 4, m, n, c_offset);
-        }
+        if (whole) *reinterpret_cast<f32x4*>(to + (size_t)it * kRowStep * p.ldc) = v * p.alpha + b;
+        else store_ragged(p, from + it * kRowStep * kPitch, 4, m, n, c_offset);   // straight from the parked row (a copy would live in scratch memory)
       }
     }
     return;
@@ -656,12 +655,8 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
       if (!active) continue;
       if (!whole) {  // ragged right edge: element by element
 #pragma unroll 1
-        for (int row = row0; row < 32 && row_base + i * 32 + row < p.M; row += kRowStep) {
-          float t[8];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) t[e] = stage[row * kPitch + c + e];
-          store_ragged(p, t, 8, row_base + i * 32 + row, n, c_offset);
-        }
+        for (int row = row0; row < 32 && row_base + i * 32 + row < p.M; row += kRowStep)
+          store_ragged(p, stage + row * kPitch + c, 8, row_base + i * 32 + row, n, c_offset);
         continue;
       }
       const size_t first = (size_t)(row_base + i * 32 + row0);
@@ -687,6 +682,100 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
   };
   using Yes = std::true_type;
   using No = std::false_type;
+  if (mode == (int)Epilogue::AffineBwdStore) {
+    // (the columns are whole 16-byte pieces here: the host accepts the mode only for N % 8 == 0)
+    const bf16_t* ysrc = static_cast<const bf16_t*>(p.affine_y);
+    float sc[8];
+    {
+      u32x4 scw = {0u, 0u, 0u, 0u};
+      if (active) scw = *reinterpret_cast<const u32x4*>(static_cast<const bf16_t*>(p.col_scale) + n);
+      unpack_bf16x8(scw, sc);
+    }
+    float s_dzy[8], s_dz[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s_dzy[e] = 0.f; s_dz[e] = 0.f; }
+    // A lane's units (8 outputs each) in order: piece by piece, kIters rows per piece.  The two per-element chunks
+    // of unit u + 2 are requested before unit u is worked out and stored: three sets of registers in rotation, and
+    // waiting for a chunk never waits for a store issued after it.
+    constexpr int kUnits = TM * kIters;
+    auto unit_row = [&](int u) { return row_base + (u / kIters) * 32 + row0 + (u % kIters) * kRowStep; };
+    u32x4 ab[3], yb[3];
+    auto request2 = [&](int u, u32x4& a, u32x4& y) {
+      if (!active) return;
+      const size_t row = (size_t)min(unit_row(u), last_row);   // a clamped, always valid row
+      a = *reinterpret_cast<const u32x4*>(xsrc + row * ldx + n);
+      y = *reinterpret_cast<const u32x4*>(ysrc + row * p.ldy + n);
+    };
+    request2(0, ab[0], yb[0]);
+    if constexpr (kUnits > 1) request2(1, ab[1], yb[1]);
+    static_for<kUnits>([&](auto u_c) {
+      constexpr int u = decltype(u_c)::value, i = u / kIters, it = u % kIters;
+      if constexpr (it == 0) park(i);
+      if constexpr (u + 2 < kUnits) request2(u + 2, ab[(u + 2) % 3], yb[(u + 2) % 3]);
+      const int row = row0 + it * kRowStep;
+      if (active && row < 32 && row_base + i * 32 + row < p.M) {
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch + 4);
+        float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]}, a[8], y[8], d[8], o[8];
+        if (scaled) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= p.alpha;
+        }
+        unpack_bf16x8(pack_bf16x8(v), d);   // the gradient as a separate pass would have read it back from memory
+        unpack_bf16x8(ab[u % 3], a);
+        unpack_bf16x8(yb[u % 3], y);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (!(a[e] > 0.f)) d[e] = 0.f;
+          s_dzy[e] += d[e] * y[e];
+          s_dz[e] += d[e];
+          o[e] = sc[e] * d[e];
+        }
+        *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.C) + c_offset + (size_t)(row_base + i * 32 + row) * p.ldc + n) = pack_bf16x8(o);
+      }
+    });
+    // Column sums: first over the lanes of this wave that share a column (their sums side by side in the wave's
+    // staging rows, added in lane order), then over the WAVES_M waves that share it, in wave order.
+    constexpr int kCols = 2 * WN;                       // [dz * y | dz] of the wave's WN columns
+    constexpr int kPerLane = (kCols + 63) / 64;
+    static_assert(kRowStep * kCols <= 32 * kPitch, "the lanes' column sums fit in the wave's staging rows");
+    asm volatile("" ::: "memory");
+    if (lane < kPerRow * kRowStep) {
+      float* mine = stage + (lane / kPerRow) * kCols + c;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { mine[e] = s_dzy[e]; mine[WN + e] = s_dz[e]; }
+    }
+    asm volatile("" ::: "memory");
+    float wave_sum[kPerLane];
+#pragma unroll
+    for (int u = 0; u < kPerLane; ++u) {
+      const int col = lane + 64 * u;
+      float t = 0.f;
+      if (col < kCols) {
+#pragma unroll
+        for (int r = 0; r < kRowStep; ++r) t += stage[r * kCols + col];
+      }
+      wave_sum[u] = t;
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int u = 0; u < kPerLane; ++u)
+      if (lane + 64 * u < kCols) stage[lane + 64 * u] = wave_sum[u];
+    __syncthreads();
+    if (wm == 0) {
+#pragma unroll
+      for (int u = 0; u < kPerLane; ++u) {
+        const int col = lane + 64 * u;
+        if (col >= kCols) continue;
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES_M; ++w) t += stage[w * (32 * kPitch) + col];   // wave wm + WAVES_M * wn: this column block's waves lie side by side
+        const int which = col / WN, cn = col_base + col % WN;
+        if (cn < p.N) p.col_partial[((size_t)tile_m * 2 + which) * p.N + cn] = t;
+      }
+    }
+    return;
+  }
   if (mode == (int)Epilogue::MaskStore) {
     run(Yes{}, No{}, [](auto, auto, float (&v)[8], const float (&x)[8], float (&)[8]) {
 #pragma unroll
@@ -875,7 +964,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
     }
   }
   float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (WN + 4));
-  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z));
+  store_wave_tile<WM, WN, WAVES_M>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z), wm, tile_m);
 }
 
 // The same product with the tile loop written as a software pipeline.  In the kernel above a wave does one thing
@@ -1090,7 +1179,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
     }
   }
   float* stage = reinterpret_cast<float*>(lds) + wave * (32 * (WN + 4));
-  store_wave_tile<WM, WN>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z));
+  store_wave_tile<WM, WN, WAVES_M>(p, acc, stage, m0 + wm * WM, n0 + wn * WN, lane, batch_offset_z(p.c_batch, z), wm, tile_m);
 }
 
 // Small products (at most a few workgroups per CU) are a chain of latencies, not a throughput problem, and the
@@ -1335,7 +1424,7 @@ template <Layout LA, Layout LB, Gather GA = Gather::None, Gather GB = Gather::No
 hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   auto tiles = [&](int tm, int tn) { return tile_count(q, tm, tn); };
   if constexpr (GA == Gather::None && GB == Gather::None) {
-    if (small_product_fits(q)) {
+    if (small_product_fits(q) && q.epilogue != Epilogue::AffineBwdStore) {   // (the small kernel's epilogue has no column sums)
       if (small_product_tile64(q)) return launch_small<64, 64, LA, LB>(q, stream);
       return launch_small<32, 32, LA, LB>(q, stream);
     }

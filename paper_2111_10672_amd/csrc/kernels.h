@@ -27,6 +27,11 @@ enum class Epilogue : int {
   BiasAct = 1,       // v = alpha * acc * col_scale[n] + bias[n]; aux_out (T) = v if given; C (T) = act(v + residual[m, n])
   MaskStore = 2,     // C (T) = mask[m, n] > 0 ? acc : 0          (ReLU backward fused into the input-gradient product)
   ScaleStore = 3,    // C (T) = acc * mask[m, n]                  (GELU backward; mask holds gelu'(pre-activation) as the forward pass stored it)
+  // Backward of "per-channel affine, then ReLU" fused into the input-gradient product that forms the gradient at the
+  // ReLU's output: d = acc rounded to T (what a separate pass would have read back), dz = mask[m, n] > 0 ? d : 0,
+  // C (T) = col_scale[n] * dz, and per tile row of the product col_partial[tile_m][0][n] = sum over its rows of
+  // dz * affine_y[m, n], col_partial[tile_m][1][n] = sum of dz (float32; reduce_pairs adds the tile rows up).
+  AffineBwdStore = 4,
 };
 
 enum class Act : int { None = 0, Relu = 1, Gelu = 2 };
@@ -82,6 +87,12 @@ struct GemmProblem {
   // along the contiguous index (lets a kernel fetch whole 16-byte chunks).
   bool a_pad_zero = false, b_pad_zero = false;
   float* a_row_sum = nullptr;     // optional [M]: sum_k A(m, k), written once by the tiles of column block 0
+  // AffineBwdStore: the affine's input (pre-affine convolution output), the partial column sums [tile rows][2][N]
+  // (room for (M + 63) / 64 tile rows) and where the launcher reports how many tile rows it wrote
+  const void* affine_y = nullptr;
+  int ldaffine_y = 0;
+  float* col_partial = nullptr;
+  int* col_partial_rows = nullptr;
   const char* name = "gemm";
 };
 

@@ -118,7 +118,7 @@ class ResnetModel : public Model {
   struct Plan {
     std::vector<UnitBuf> unit;   // stem, blocks
     size_t pooled, logits, row_loss, dlogits, dpooled;
-    size_t g[8];                 // backward transients: gradients of activations
+    size_t g[9];                 // backward transients: gradients of activations
     static constexpr int kReduceSlots = 4;   // a unit has at most three convolutions and a projection
     size_t affine_partial[kReduceSlots], wgrad_partial[kReduceSlots];
     size_t total;
@@ -202,6 +202,7 @@ class ResnetModel : public Model {
       size_t ap = 0, wp = 0;
       auto see = [&](const Conv& c) {
         ap = std::max(ap, affine_partial_floats(c.out_rows(batch_), c.cout) * 4);
+        ap = std::max(ap, (size_t)((c.out_rows(batch_) + 63) / 64) * 2 * c.cout * 4);   // the fused form: one row of sums per tile row
         wp = std::max(wp, (size_t)wgrad_splits(c) * c.cout * c.k_total() * 4);
       };
       see(stem_);
@@ -255,6 +256,37 @@ class ResnetModel : public Model {
     g.residual = residual; g.ldres = c.cin_eff;
     g.name = "conv_dgrad";
     return gemm(g, s);
+  }
+  // The input-gradient product of convolution c with the backward pass of the affine + ReLU below it (`below`, whose
+  // output `act` is c's input and whose input is `y`) in its epilogue: dy_below = scale * (dx * [act > 0]) and the
+  // column sums for dscale, dshift, without the gradient dx ever being written.  Returns 1 if the product cannot
+  // take that epilogue (the caller then runs the two passes), 0 or an error code otherwise.
+  int conv_dgrad_affine(const Conv& c, const void* dy, const void* w, const Conv& below, const void* act, const void* y, void* dy_below,
+                        float* partial, hipStream_t s) {
+    GemmProblem g;
+    g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::KRow; g.epilogue = Epilogue::AffineBwdStore;
+    if (!pointwise(c)) {
+      g.a_gather = Gather::ConvRows; g.b_gather = Gather::ConvWeightT;
+      g.conv.n = batch_; g.conv.sh = c.out_h; g.conv.sw = c.out_w; g.conv.sc = c.cout; g.conv.rh = c.in_h; g.conv.rw = c.in_w;
+      g.conv.r = c.k; g.conv.s = c.k; g.conv.stride = c.stride; g.conv.pad = c.pad; g.conv.transposed = 1;
+      g.conv.w_cin = c.cin_eff; g.conv.w_cout = c.cout;
+    }
+    g.M = (int)c.in_rows(batch_); g.N = c.cin_eff; g.K = c.k * c.k * c.cout;
+    g.A = dy; g.lda = g.K; g.B = w; g.ldb = c.cin_eff; g.C = dy_below; g.ldc = c.cin_eff;
+    g.mask = act; g.ldmask = c.cin_eff; g.affine_y = y; g.ldaffine_y = c.cin_eff; g.col_scale = param_ptrs[below.scale];
+    g.col_partial = partial;
+    g.col_partial_rows = &fused_tile_rows_;   // (a member: the product may be replayed later from its recorded description)
+    g.name = "conv_dgrad_affine";
+    if (c.cin_eff != below.cout || !gemm_dma_accepts(g)) return 1;
+    if (int rc = gemm(g, s)) return rc;
+    ReduceTask task;
+    const int tile_rows = fused_tile_rows_;
+    task.kind = ReduceTask::kPairs; task.partial = partial; task.count = tile_rows; task.width = below.cout;
+    task.out = static_cast<float*>(grad_ptrs[below.scale]); task.out_b = static_cast<float*>(grad_ptrs[below.shift]);
+    task.blocks = (unsigned)((2 * below.cout + 3) / 4);
+    reduce_bytes_ += (double)tile_rows * 2 * below.cout * 4;
+    reduces_.push_back(task);
+    return SPB_OK;
   }
   // dw = sum over pixels of dy (x) x-patch, as k-slices added up in a fixed order
   int conv_wgrad(const Conv& c, const void* x, const void* dy, float* partial, float* dw, hipStream_t s) {
@@ -395,22 +427,31 @@ class ResnetModel : public Model {
       void* da = w + p.g[4];
       const int last = (int)b.convs.size() - 1;
       // Weight gradients run on the side stream, beside the chain of input gradients.  They read the gradient
-      // buffers dy alternates between (slots 3 and 5) and slot 6; the block above may still be reading them.
+      // buffers dy rotates through (slots 3, 5 and 8) and slot 6; the block above may still be reading them.
       if (int rc = join(s)) return rc;
-      int reader[2] = {-1, -1};   // mark of the weight-gradient product that last read slot 3 / slot 5
-      int dy_slot = 0;            // dy lives in slot 3 + 2 * dy_slot
+      // dy rotates through three buffers (slots 3, 5, 8): a fused input-gradient product writes the next dy while the
+      // weight gradient forked one convolution earlier may still be reading the one before, and with three the buffer
+      // it writes was last read two forks ago.
+      constexpr int kDySlots[3] = {3, 5, 8};
+      int reader[3] = {-1, -1, -1};   // mark of the weight-gradient product that last read each of them
+      int dy_slot = 0;                // dy lives in slot kDySlots[dy_slot]
       // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut
       if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart(last), s)) return rc;
       for (int j = last; j >= 1; --j) {
         const void* in_j = w + u.conv[j - 1].a;
         if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart(j), static_cast<float*>(grad_ptrs[b.convs[j].w]), fork(s))) return rc;
         reader[dy_slot] = mark();
-        if (int rc = conv_dgrad(b.convs[j], dy, param_ptrs[b.convs[j].w], nullptr, da, s)) return rc;
-        const int next_slot = dy_slot ^ 1;
-        void* dy_next = w + p.g[3 + 2 * next_slot];
+        const int next_slot = (dy_slot + 1) % 3;
+        void* dy_next = w + p.g[kDySlots[next_slot]];
         if (int rc = wait_mark(s, reader[next_slot])) return rc;   // whoever read that slot is done with it
         reader[next_slot] = -1;
-        if (int rc = affine_bwd(b.convs[j - 1], da, in_j, w + u.conv[j - 1].y, dy_next, nullptr, apart(j - 1), s)) return rc;
+        // the gradient at convolution j's input only feeds the affine + ReLU below: one pass where the product can take it
+        const int fused = conv_dgrad_affine(b.convs[j], dy, param_ptrs[b.convs[j].w], b.convs[j - 1], in_j, w + u.conv[j - 1].y, dy_next, apart(j - 1), s);
+        if (fused < 0) return fused;
+        if (fused > 0) {
+          if (int rc = conv_dgrad(b.convs[j], dy, param_ptrs[b.convs[j].w], nullptr, da, s)) return rc;
+          if (int rc = affine_bwd(b.convs[j - 1], da, in_j, w + u.conv[j - 1].y, dy_next, nullptr, apart(j - 1), s)) return rc;
+        }
         dy = dy_next;
         dy_slot = next_slot;
       }
@@ -489,6 +530,7 @@ class ResnetModel : public Model {
   int fc_w_ = -1, fc_b_ = -1;
   const void* x_ = nullptr;
   std::vector<ReduceTask> reduces_;   // of the unit whose backward pass is being enqueued
+  int fused_tile_rows_ = 0;
   double reduce_bytes_ = 0.0;
 };
 
