@@ -58,7 +58,7 @@ class EncoderModel : public Model {
     std::vector<size_t> xout;        // output of unit u, u = 0..NL
     std::vector<LayerBuf> layer;     // per layer: own stash or the shared scratch
     size_t scores, y, statsf, logits, row_loss, dlogits;
-    size_t dy, partial, dx[2], dF, dv, dh, dctx, dscore, dqkv, du;
+    size_t dy, partial, dx[2], dF[2], dv, dh[2], dctx, dscore, dqkv[2], du;
     size_t total;
   };
 
@@ -83,14 +83,15 @@ class EncoderModel : public Model {
     p.scores = take(zss * 4);
     p.y = take((size_t)R * H * 2); p.statsf = take((size_t)R * 8); p.logits = take((size_t)R * ldz() * 4);
     p.row_loss = take((size_t)R * 4); p.dlogits = take((size_t)R * ldv() * 2);
-    p.dy = p.partial = p.dx[0] = p.dx[1] = p.dF = p.dv = p.dh = p.dctx = p.dscore = p.dqkv = p.du = 0;
+    p.dy = p.partial = p.dx[0] = p.dx[1] = p.dF[0] = p.dF[1] = p.dv = p.dh[0] = p.dh[1] = p.dctx = p.dscore = p.dqkv[0] = p.dqkv[1] = p.du = 0;
     if (k >= 1) {
       p.dy = take((size_t)R * H * 2);
       p.partial = take(std::max(layernorm_partial_floats(M, H), layernorm_partial_floats(R, H)) * 4);
     }
     if (k >= 2) {
-      p.dx[0] = take(mh); p.dx[1] = take(mh); p.dF = take(mf); p.dv = take(mh); p.dh = take(mh); p.dctx = take(mh);
-      p.dscore = take(zss * 2); p.dqkv = take(3 * mh); p.du = take(mh);
+      // dF, dh and dqkv are read by weight gradients on the second stream: two of each, used by alternate layers
+      p.dx[0] = take(mh); p.dx[1] = take(mh); p.dF[0] = take(mf); p.dF[1] = take(mf); p.dv = take(mh); p.dh[0] = take(mh); p.dh[1] = take(mh);
+      p.dctx = take(mh); p.dscore = take(zss * 2); p.dqkv[0] = take(3 * mh); p.dqkv[1] = take(3 * mh); p.du = take(mh);
     }
     p.total = off;
     return p;
@@ -242,6 +243,7 @@ class EncoderModel : public Model {
           return launch_layernorm_bwd(w + p.dy, H, w + p.xout[NL], H, rows_, reinterpret_cast<const float*>(w + p.statsf), param_ptrs[hp(0)],
                                       nullptr, 0, dout, H, partial, G(hp(0)), G(hp(1)), R, H, s); })) return rc;
     int which = 0;  // dout lives in p.dx[which]
+    std::vector<int> ffn_done(NL, -1), side_done(NL, -1);   // marks on the second stream: after a layer's first / second pair of weight gradients
 
     // ---- encoder layers, top down ----
     for (int i = NL - 1; i >= 0 && i + 1 >= cut; --i) {
@@ -250,29 +252,37 @@ class EncoderModel : public Model {
       const void* xin = w + p.xout[i];
       auto P = [&](int j) { return param_ptrs[lp(i, j)]; };
       auto GP = [&](int j) { return G(lp(i, j)); };
-      // The previous layer's weight gradients read dF, dh and dqkv, which this layer is about to overwrite.
-      if (int rc = join(s)) return rc;
+      // Weight gradients on the second stream read dF, dh, dqkv and the layer's incoming gradient.  Alternate layers use
+      // alternate copies of the first three, so this layer only has to know that the weight gradients of the layer
+      // two above are done - which they are long since; a join here would stall the chain behind the previous
+      // layer's weight gradients at every layer.
+      char* dF = w + p.dF[i & 1];
+      char* dh = w + p.dh[i & 1];
+      char* dqkv = w + p.dqkv[i & 1];
+      if (i + 2 < NL)
+        if (int rc = wait_mark(s, side_done[i + 2])) return rc;
       // feed-forward half
       {
-        GemmProblem g = dgrad(dout, H, M, P(W2W), H, F, w + p.dF, F);   // dz1 = (dout W2) * gelu'(z1), the factor as stashed
+        GemmProblem g = dgrad(dout, H, M, P(W2W), H, F, dF, F);   // dz1 = (dout W2) * gelu'(z1), the factor as stashed
         g.epilogue = Epilogue::ScaleStore; g.mask = w + b.z1; g.ldmask = F;
         if (int rc = gemm(g, s)) return rc;
       }
       {
         hipStream_t side = fork(s);   // one fork for both weight gradients of the feed-forward half: each fork costs a few microseconds
         if (int rc = gemm(wgrad(dout, H, w + b.f, F, M, H, F, GP(W2W), GP(W2B)), side)) return rc;
-        if (int rc = gemm(wgrad(w + p.dF, F, w + b.v, H, M, F, H, GP(W1W), GP(W1B)), side)) return rc;
+        if (int rc = gemm(wgrad(dF, F, w + b.v, H, M, F, H, GP(W1W), GP(W1B)), side)) return rc;
+        ffn_done[i] = mark();
       }
-      if (int rc = gemm(dgrad(w + p.dF, F, M, P(W1W), F, H, w + p.dv, H), s)) return rc;
+      if (int rc = gemm(dgrad(dF, F, M, P(W1W), F, H, w + p.dv, H), s)) return rc;
       if (int rc = run("layernorm_bwd", 4 * mh, s, [&] {   // dh = dout + LN2 backward
             return launch_layernorm_bwd(w + p.dv, H, w + b.h, H, nullptr, reinterpret_cast<const float*>(w + b.stats2), P(LN2W), dout, H,
-                                        w + p.dh, H, partial, GP(LN2W), GP(LN2B), M, H, s); })) return rc;
+                                        dh, H, partial, GP(LN2W), GP(LN2B), M, H, s); })) return rc;
       // attention half
-      if (int rc = gemm(dgrad(w + p.dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
+      if (int rc = gemm(dgrad(dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
       const char* qbase = w + b.qkv;
       if (attention_fused_accepts(S, D, 3 * H, H)) {
         if (int rc = run("attention_bwd", (double)M * H * 2 * 7 + (double)Z * S * S * 2, s, [&] {
-              return launch_attention_bwd(qbase, 3 * H, w + b.prob, w + p.dctx, H, w + p.dqkv, B, NH, S, D, inv_sqrt_d, s); })) return rc;
+              return launch_attention_bwd(qbase, 3 * H, w + b.prob, w + p.dctx, H, dqkv, B, NH, S, D, inv_sqrt_d, s); })) return rc;
       } else {
       {
         GemmProblem g;  // dP[s, s'] = dctx[s, :] . V[s', :]
@@ -291,7 +301,7 @@ class EncoderModel : public Model {
         g.M = S; g.N = D; g.K = S; g.A = a; g.lda = lda; g.a_batch = ab;
         g.B = bsrc; g.ldb = (bsrc == (const void*)(w + p.dctx)) ? H : 3 * H;
         g.b_batch = per_head(g.ldb);
-        g.C = bf(w + p.dqkv, (size_t)col_block * H); g.ldc = 3 * H; g.c_batch = per_head(3 * H);
+        g.C = bf(dqkv, (size_t)col_block * H); g.ldc = 3 * H; g.c_batch = per_head(3 * H);
         g.batch = Z; g.name = name;
         return gemm(g, s);
       };
@@ -302,13 +312,17 @@ class EncoderModel : public Model {
       }
       {
         hipStream_t side = fork(s);   // and one for the attention half
-        if (int rc = gemm(wgrad(w + p.dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), side)) return rc;
-        if (int rc = gemm(wgrad(w + p.dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), side)) return rc;
+        if (int rc = gemm(wgrad(dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), side)) return rc;
+        if (int rc = gemm(wgrad(dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), side)) return rc;
+        side_done[i] = mark();
       }
-      if (int rc = gemm(dgrad(w + p.dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
+      if (int rc = gemm(dgrad(dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
       void* dx = lowest ? nullptr : w + p.dx[which ^ 1];
+      // dx lands where the layer above found its incoming gradient, which that layer's feed-forward weight gradient reads
+      if (dx && i + 1 < NL)
+        if (int rc = wait_mark(s, ffn_done[i + 1])) return rc;
       if (int rc = run("layernorm_bwd", (lowest ? 2 : 4) * mh, s, [&] {   // dx = dh + LN1 backward; the lowest unit forms no input gradient
-            return launch_layernorm_bwd(w + p.du, H, xin, H, nullptr, reinterpret_cast<const float*>(w + b.stats1), P(LN1W), w + p.dh, H,
+            return launch_layernorm_bwd(w + p.du, H, xin, H, nullptr, reinterpret_cast<const float*>(w + b.stats1), P(LN1W), dh, H,
                                         dx, H, partial, GP(LN1W), GP(LN1B), M, H, s); })) return rc;
       dout = dx;
       which ^= 1;
