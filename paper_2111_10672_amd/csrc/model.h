@@ -85,7 +85,7 @@ class Model {
   int join(hipStream_t s);
   // Finer than join: mark() stands for everything enqueued on the side stream so far (-1 when nothing is forked),
   // wait_mark(s, m) makes s wait for just that.  At most kMarks marks are live at a time.
-  static constexpr int kMarks = 8;
+  static constexpr int kMarks = 16;
   int mark();
   int wait_mark(hipStream_t s, int m);
   int gemm(const GemmProblem& p, hipStream_t s);
@@ -95,7 +95,7 @@ class Model {
 
  private:
   hipStream_t side_ = nullptr;
-  hipEvent_t fork_ev_ = nullptr, join_ev_ = nullptr, mark_ev_[8] = {};
+  hipEvent_t fork_ev_ = nullptr, join_ev_ = nullptr, mark_ev_[kMarks] = {};
   int next_mark_ = 0;
   bool forked_ = false;
 };

@@ -118,9 +118,9 @@ class ResnetModel : public Model {
   struct Plan {
     std::vector<UnitBuf> unit;   // stem, blocks
     size_t pooled, logits, row_loss, dlogits, dpooled;
-    size_t g[9];                 // backward transients: gradients of activations
+    size_t g[13];                // backward transients: gradients of activations
     static constexpr int kReduceSlots = 4;   // a unit has at most three convolutions and a projection
-    size_t affine_partial[kReduceSlots], wgrad_partial[kReduceSlots];
+    size_t affine_partial[2][kReduceSlots], wgrad_partial[2][kReduceSlots];   // two sets: alternate units use alternate ones
     size_t total;
   };
   static constexpr int kFwdPool = 8;
@@ -196,7 +196,8 @@ class ResnetModel : public Model {
     p.dlogits = take((size_t)batch_ * align_up((size_t)classes_, 8) * 2);
     p.dpooled = take((size_t)batch_ * features_ * 2);
     for (auto& g : p.g) g = 0;
-    for (int j = 0; j < Plan::kReduceSlots; ++j) p.affine_partial[j] = p.wgrad_partial[j] = 0;
+    for (int h = 0; h < 2; ++h)
+      for (int j = 0; j < Plan::kReduceSlots; ++j) p.affine_partial[h][j] = p.wgrad_partial[h][j] = 0;
     if (k >= 2) {
       for (auto& g : p.g) g = take(amax);
       size_t ap = 0, wp = 0;
@@ -208,7 +209,8 @@ class ResnetModel : public Model {
       see(stem_);
       for (const Block& b : blocks_) { for (const Conv& c : b.convs) see(c); if (b.has_proj) see(b.proj); }
       // one buffer of each kind per convolution of a unit: their reductions wait for the unit's end (see backward)
-      for (int j = 0; j < Plan::kReduceSlots; ++j) { p.affine_partial[j] = take(ap); p.wgrad_partial[j] = take(wp); }
+      for (int h = 0; h < 2; ++h)
+        for (int j = 0; j < Plan::kReduceSlots; ++j) { p.affine_partial[h][j] = take(ap); p.wgrad_partial[h][j] = take(wp); }
     }
     p.total = off;
     return p;
@@ -391,8 +393,10 @@ class ResnetModel : public Model {
     const int cut = num_units - k;
     const int lddz = (int)align_up((size_t)classes_, 8), hw = final_h_ * final_w_;
     // partial-sum buffers of a unit's convolutions: slot j for convolution j, the last slot for the projection
-    auto apart = [&](int j) { return reinterpret_cast<float*>(w + p.affine_partial[j]); };
-    auto wpart = [&](int j) { return reinterpret_cast<float*>(w + p.wgrad_partial[j]); };
+    int half = 0;   // which set of the buffers the second stream reads the unit at hand uses (alternates from unit to unit)
+    auto apart = [&](int j) { return reinterpret_cast<float*>(w + p.affine_partial[half][j]); };
+    auto wpart = [&](int j) { return reinterpret_cast<float*>(w + p.wgrad_partial[half][j]); };
+    std::vector<int> unit_done(blocks_.size(), -1);   // marks on the second stream: a unit's last work there
     constexpr int kProjSlot = Plan::kReduceSlots - 1;
     reduces_.clear();
     reduce_bytes_ = 0.0;
@@ -422,17 +426,22 @@ class ResnetModel : public Model {
       const UnitBuf& u = p.unit[i + 1];
       const bool need_dx = i + 1 > cut;
       const void* x_in = w + p.unit[i].out;
+      // Weight gradients and the unit's small reductions run on the second stream, beside the chain of input gradients.
+      // What they read and this chain writes (the dy buffers, the projection's dy, the partial sums) exists twice and
+      // alternate units use alternate copies, so this unit only has to know that the second stream is done with the
+      // unit two above - which it is long since; a join here would stall the chain behind the previous unit's weight
+      // gradients at every unit.
+      half = i & 1;
+      if (i + 2 < (int)blocks_.size())
+        if (int rc = wait_mark(s, unit_done[i + 2])) return rc;
       void* dsum = w + p.g[2];
-      void* dy = w + p.g[3];
       void* da = w + p.g[4];
       const int last = (int)b.convs.size() - 1;
-      // Weight gradients run on the side stream, beside the chain of input gradients.  They read the gradient
-      // buffers dy rotates through (slots 3, 5 and 8) and slot 6; the block above may still be reading them.
-      if (int rc = join(s)) return rc;
-      // dy rotates through three buffers (slots 3, 5, 8): a fused input-gradient product writes the next dy while the
-      // weight gradient forked one convolution earlier may still be reading the one before, and with three the buffer
-      // it writes was last read two forks ago.
-      constexpr int kDySlots[3] = {3, 5, 8};
+      // dy rotates through three buffers: a fused input-gradient product writes the next dy while the weight gradient
+      // forked one convolution earlier may still be reading the one before, and with three the buffer it writes was
+      // last read two forks ago.
+      const int kDySlots[3] = {half ? 9 : 3, half ? 10 : 5, half ? 11 : 8};
+      void* dy = w + p.g[kDySlots[0]];
       int reader[3] = {-1, -1, -1};   // mark of the weight-gradient product that last read each of them
       int dy_slot = 0;                // dy lives in slot kDySlots[dy_slot]
       // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut
@@ -456,7 +465,7 @@ class ResnetModel : public Model {
         dy_slot = next_slot;
       }
       const void* shortcut_grad = dsum;
-      void* dys = w + p.g[6];
+      void* dys = w + p.g[half ? 12 : 6];
       if (b.has_proj)
         if (int rc = affine_bwd(b.proj, dsum, nullptr, w + u.proj.y, dys, nullptr, apart(kProjSlot), s)) return rc;
       {
@@ -467,6 +476,7 @@ class ResnetModel : public Model {
         if (b.has_proj)
           if (int rc = conv_wgrad(b.proj, x_in, dys, wpart(kProjSlot), static_cast<float*>(grad_ptrs[b.proj.w]), side)) return rc;
         if (int rc = flush_reduces(side)) return rc;
+        unit_done[i] = mark();
       }
       if (b.has_proj) {
         if (need_dx) {
