@@ -313,7 +313,10 @@ class EncoderModel : public Model {
       {
         hipStream_t side = fork(s);   // and one for the attention half
         if (int rc = gemm(wgrad(dh, H, w + b.ctx, H, M, H, H, GP(OUTW), GP(OUTB)), side)) return rc;
-        if (int rc = gemm(wgrad(dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), side)) return rc;
+        // (the lowest layer's goes behind its LayerNorm on the chain itself, which has nothing else left to do, so
+        // that the step does not end on two weight gradients in a row on the second stream)
+        if (!lowest)
+          if (int rc = gemm(wgrad(dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), side)) return rc;
         side_done[i] = mark();
       }
       if (int rc = gemm(dgrad(dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
@@ -324,6 +327,8 @@ class EncoderModel : public Model {
       if (int rc = run("layernorm_bwd", (lowest ? 2 : 4) * mh, s, [&] {   // dx = dh + LN1 backward; the lowest unit forms no input gradient
             return launch_layernorm_bwd(w + p.du, H, xin, H, nullptr, reinterpret_cast<const float*>(w + b.stats1), P(LN1W), dh, H,
                                         dx, H, partial, GP(LN1W), GP(LN1B), M, H, s); })) return rc;
+      if (lowest)
+        if (int rc = gemm(wgrad(dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), s)) return rc;
       dout = dx;
       which ^= 1;
     }
