@@ -42,7 +42,7 @@ bool gemm_dma_accepts(const GemmProblem& p) {
   if (reads_mask && (!p.mask || p.ldmask % 8 || !a16(p.mask))) return false;
   if (p.epilogue == Epilogue::AffineBwdStore &&
       (!p.mask || p.ldmask % 8 || !a16(p.mask) || !p.affine_y || p.ldaffine_y % 8 || !a16(p.affine_y) || !p.col_scale || !p.col_partial ||
-       p.N % 8 || p.k_splits != 1 || p.batch != 1 || p.bias || p.residual || p.aux_out))
+       p.N % 8 || p.k_splits != 1 || p.batch != 1 || p.bias))
     return false;
   if (p.residual && (p.ldres % 8 || !a16(p.residual))) return false;
   if (p.aux_out && (p.ldaux % 8 || !a16(p.aux_out))) return false;

@@ -699,19 +699,24 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
     // waiting for a chunk never waits for a store issued after it.
     constexpr int kUnits = TM * kIters;
     auto unit_row = [&](int u) { return row_base + (u / kIters) * 32 + row0 + (u % kIters) * kRowStep; };
-    u32x4 ab[3], yb[3];
-    auto request2 = [&](int u, u32x4& a, u32x4& y) {
+    // Optional: a second gradient that joins the product before the rounding (the shortcut's, where the product is a
+    // unit's last input gradient) and a copy of dz itself (what that unit hands down its own shortcut).
+    const bf16_t* rsrc = static_cast<const bf16_t*>(p.residual);
+    bf16_t* dz_out = static_cast<bf16_t*>(p.aux_out);
+    u32x4 ab[3], yb[3], rb[3];
+    auto request2 = [&](int u, u32x4& a, u32x4& y, u32x4& r) {
       if (!active) return;
       const size_t row = (size_t)min(unit_row(u), last_row);   // a clamped, always valid row
       a = *reinterpret_cast<const u32x4*>(xsrc + row * ldx + n);
       y = *reinterpret_cast<const u32x4*>(ysrc + row * p.ldy + n);
+      if (rsrc) r = *reinterpret_cast<const u32x4*>(rsrc + row * p.ldres + n);
     };
-    request2(0, ab[0], yb[0]);
-    if constexpr (kUnits > 1) request2(1, ab[1], yb[1]);
+    request2(0, ab[0], yb[0], rb[0]);
+    if constexpr (kUnits > 1) request2(1, ab[1], yb[1], rb[1]);
     static_for<kUnits>([&](auto u_c) {
       constexpr int u = decltype(u_c)::value, i = u / kIters, it = u % kIters;
       if constexpr (it == 0) park(i);
-      if constexpr (u + 2 < kUnits) request2(u + 2, ab[(u + 2) % 3], yb[(u + 2) % 3]);
+      if constexpr (u + 2 < kUnits) request2(u + 2, ab[(u + 2) % 3], yb[(u + 2) % 3], rb[(u + 2) % 3]);
       const int row = row0 + it * kRowStep;
       if (active && row < 32 && row_base + i * 32 + row < p.M) {
         const f32x4 v0 = *reinterpret_cast<const f32x4*>(from + it * kRowStep * kPitch);
@@ -720,6 +725,12 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
         if (scaled) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] *= p.alpha;
+        }
+        if (rsrc) {
+          float r[8];
+          unpack_bf16x8(rb[u % 3], r);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += r[e];
         }
         unpack_bf16x8(pack_bf16x8(v), d);   // the gradient as a separate pass would have read it back from memory
         unpack_bf16x8(ab[u % 3], a);
@@ -731,7 +742,9 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
           s_dz[e] += d[e];
           o[e] = sc[e] * d[e];
         }
-        *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.C) + c_offset + (size_t)(row_base + i * 32 + row) * p.ldc + n) = pack_bf16x8(o);
+        const size_t m = (size_t)(row_base + i * 32 + row);
+        if (dz_out) *reinterpret_cast<u32x4*>(dz_out + m * p.ldaux + n) = pack_bf16x8(d);   // exact: d is bfloat16 already
+        *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(p.C) + c_offset + m * p.ldc + n) = pack_bf16x8(o);
       }
     });
     // Column sums: first over the lanes of this wave that share a column (their sums side by side in the wave's

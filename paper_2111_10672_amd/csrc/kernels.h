@@ -31,6 +31,7 @@ enum class Epilogue : int {
   // ReLU's output: d = acc rounded to T (what a separate pass would have read back), dz = mask[m, n] > 0 ? d : 0,
   // C (T) = col_scale[n] * dz, and per tile row of the product col_partial[tile_m][0][n] = sum over its rows of
   // dz * affine_y[m, n], col_partial[tile_m][1][n] = sum of dz (float32; reduce_pairs adds the tile rows up).
+  // With residual: d = acc + residual[m, n] before the rounding; with aux_out: aux_out (T) = dz.
   AffineBwdStore = 4,
 };
 

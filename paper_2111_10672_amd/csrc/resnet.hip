@@ -118,9 +118,14 @@ class ResnetModel : public Model {
   struct Plan {
     std::vector<UnitBuf> unit;   // stem, blocks
     size_t pooled, logits, row_loss, dlogits, dpooled;
-    size_t g[13];                // backward transients: gradients of activations
+    // backward transients, gradients of activations: 0, 1 the gradient handed from unit to unit where it is stored
+    // unmasked (the top unit's, the stem's), 2 a convolution's input gradient on its way to an unfused affine pass,
+    // 3 the projection's input gradient; then three sets (units i % 3) of: dy (three in rotation), the projection's
+    // dy, and the unit's masked output gradient (what its shortcut carries)
+    static constexpr int kSets = 3, kSetBase = 4, kPerSet = 5;
+    size_t g[kSetBase + kSets * kPerSet];
     static constexpr int kReduceSlots = 4;   // a unit has at most three convolutions and a projection
-    size_t affine_partial[2][kReduceSlots], wgrad_partial[2][kReduceSlots];   // two sets: alternate units use alternate ones
+    size_t affine_partial[kSets][kReduceSlots], wgrad_partial[kSets][kReduceSlots];   // per set of units
     size_t total;
   };
   static constexpr int kFwdPool = 8;
@@ -196,7 +201,7 @@ class ResnetModel : public Model {
     p.dlogits = take((size_t)batch_ * align_up((size_t)classes_, 8) * 2);
     p.dpooled = take((size_t)batch_ * features_ * 2);
     for (auto& g : p.g) g = 0;
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < Plan::kSets; ++h)
       for (int j = 0; j < Plan::kReduceSlots; ++j) p.affine_partial[h][j] = p.wgrad_partial[h][j] = 0;
     if (k >= 2) {
       for (auto& g : p.g) g = take(amax);
@@ -209,7 +214,7 @@ class ResnetModel : public Model {
       see(stem_);
       for (const Block& b : blocks_) { for (const Conv& c : b.convs) see(c); if (b.has_proj) see(b.proj); }
       // one buffer of each kind per convolution of a unit: their reductions wait for the unit's end (see backward)
-      for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < Plan::kSets; ++h)
         for (int j = 0; j < Plan::kReduceSlots; ++j) { p.affine_partial[h][j] = take(ap); p.wgrad_partial[h][j] = take(wp); }
     }
     p.total = off;
@@ -259,12 +264,23 @@ class ResnetModel : public Model {
     g.name = "conv_dgrad";
     return gemm(g, s);
   }
+  // Whether unit i + 1's (block i's) last input-gradient product also does the affine pass at the output of the unit
+  // below: the tensor shapes must chain and the columns must be whole 16-byte pieces.
+  bool fuses_into_unit_below(int i) const {
+    if (i < 1) return false;   // below the first block lies the stem (and possibly a pooling layer)
+    const Conv& c = blocks_[i].convs[0];
+    const Conv& below = blocks_[i - 1].convs.back();
+    return c.cin_eff == below.cout && c.cin_eff % 8 == 0 && c.in_rows(batch_) == below.out_rows(batch_);
+  }
   // The input-gradient product of convolution c with the backward pass of the affine + ReLU below it (`below`, whose
   // output `act` is c's input and whose input is `y`) in its epilogue: dy_below = scale * (dx * [act > 0]) and the
   // column sums for dscale, dshift, without the gradient dx ever being written.  Returns 1 if the product cannot
   // take that epilogue (the caller then runs the two passes), 0 or an error code otherwise.
+  // With `residual` (a second gradient of the same tensor: the shortcut's) the sum of the two is what the ReLU masks,
+  // and dz_out (optional) receives that masked sum: the form for a unit's LAST input gradient, which then also does
+  // the affine pass at the output of the unit below.
   int conv_dgrad_affine(const Conv& c, const void* dy, const void* w, const Conv& below, const void* act, const void* y, void* dy_below,
-                        float* partial, hipStream_t s) {
+                        float* partial, hipStream_t s, const void* residual = nullptr, void* dz_out = nullptr) {
     GemmProblem g;
     g.dtype = dtype; g.a_layout = Layout::RowK; g.b_layout = Layout::KRow; g.epilogue = Epilogue::AffineBwdStore;
     if (!pointwise(c)) {
@@ -277,6 +293,7 @@ class ResnetModel : public Model {
     g.A = dy; g.lda = g.K; g.B = w; g.ldb = c.cin_eff; g.C = dy_below; g.ldc = c.cin_eff;
     g.mask = act; g.ldmask = c.cin_eff; g.affine_y = y; g.ldaffine_y = c.cin_eff; g.col_scale = param_ptrs[below.scale];
     g.col_partial = partial;
+    g.residual = residual; g.ldres = c.cin_eff; g.aux_out = dz_out; g.ldaux = c.cin_eff;
     g.col_partial_rows = &fused_tile_rows_;   // (a member: the product may be replayed later from its recorded description)
     g.name = "conv_dgrad_affine";
     if (c.cin_eff != below.cout || !gemm_dma_accepts(g)) return 1;
@@ -393,9 +410,11 @@ class ResnetModel : public Model {
     const int cut = num_units - k;
     const int lddz = (int)align_up((size_t)classes_, 8), hw = final_h_ * final_w_;
     // partial-sum buffers of a unit's convolutions: slot j for convolution j, the last slot for the projection
-    int half = 0;   // which set of the buffers the second stream reads the unit at hand uses (alternates from unit to unit)
-    auto apart = [&](int j) { return reinterpret_cast<float*>(w + p.affine_partial[half][j]); };
-    auto wpart = [&](int j) { return reinterpret_cast<float*>(w + p.wgrad_partial[half][j]); };
+    int set = 0;   // which set of the buffers the second stream reads the unit at hand uses: unit i uses set i % 3
+    auto apart_of = [&](int st, int j) { return reinterpret_cast<float*>(w + p.affine_partial[st][j]); };
+    auto apart = [&](int j) { return apart_of(set, j); };
+    auto wpart = [&](int j) { return reinterpret_cast<float*>(w + p.wgrad_partial[set][j]); };
+    auto G = [&](int st, int which) { return w + p.g[Plan::kSetBase + st * Plan::kPerSet + which]; };   // which: 0-2 dy, 3 the projection's dy, 4 the masked output gradient
     std::vector<int> unit_done(blocks_.size(), -1);   // marks on the second stream: a unit's last work there
     constexpr int kProjSlot = Plan::kReduceSlots - 1;
     reduces_.clear();
@@ -419,6 +438,7 @@ class ResnetModel : public Model {
     }
     void* dout = w + p.g[0];
     int dout_slot = 0;
+    bool incoming_fused = false;   // the unit above has already done this unit's output affine pass
     if (int rc = run("avgpool_bwd", (double)batch_ * hw * features_ * 2, s, [&] { return launch_avgpool_bwd(w + p.dpooled, dout, batch_, hw, features_, s); })) return rc;
     // ---- residual blocks, top down ----
     for (int i = (int)blocks_.size() - 1; i >= 0 && i + 1 >= cut; --i) {
@@ -427,31 +447,34 @@ class ResnetModel : public Model {
       const bool need_dx = i + 1 > cut;
       const void* x_in = w + p.unit[i].out;
       // Weight gradients and the unit's small reductions run on the second stream, beside the chain of input gradients.
-      // What they read and this chain writes (the dy buffers, the projection's dy, the partial sums) exists twice and
-      // alternate units use alternate copies, so this unit only has to know that the second stream is done with the
-      // unit two above - which it is long since; a join here would stall the chain behind the previous unit's weight
-      // gradients at every unit.
-      half = i & 1;
-      if (i + 2 < (int)blocks_.size())
-        if (int rc = wait_mark(s, unit_done[i + 2])) return rc;
-      void* dsum = w + p.g[2];
-      void* da = w + p.g[4];
+      // What they read and this chain writes (the dy buffers, the projection's dy, the partial sums, the masked output
+      // gradient) exists three times, unit i uses set i % 3 and the unit above already writes into the set of the
+      // unit below (see the end of this loop), so the chain only has to know that the second stream is done with the
+      // units three (here) and two (there) above - which it is long since; a join here would stall the chain behind
+      // the previous unit's weight gradients at every unit.
+      set = i % Plan::kSets;
+      if (i + 3 < (int)blocks_.size())
+        if (int rc = wait_mark(s, unit_done[i + 3])) return rc;
+      void* dsum = G(set, 4);
+      void* da = w + p.g[2];
       const int last = (int)b.convs.size() - 1;
       // dy rotates through three buffers: a fused input-gradient product writes the next dy while the weight gradient
       // forked one convolution earlier may still be reading the one before, and with three the buffer it writes was
       // last read two forks ago.
-      const int kDySlots[3] = {half ? 9 : 3, half ? 10 : 5, half ? 11 : 8};
-      void* dy = w + p.g[kDySlots[0]];
+      void* const dy_slots[3] = {G(set, 0), G(set, 1), G(set, 2)};
+      void* dy = dy_slots[0];
       int reader[3] = {-1, -1, -1};   // mark of the weight-gradient product that last read each of them
       int dy_slot = 0;                // dy lives in slot kDySlots[dy_slot]
-      // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut
-      if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart(last), s)) return rc;
+      // the block's output gradient, masked by its ReLU, feeds the last convolution's affine and the shortcut (where
+      // the unit above could fuse that pass into its last product, dy and dsum are there already)
+      if (!incoming_fused)
+        if (int rc = affine_bwd(b.convs[last], dout, w + u.out, w + u.conv[last].y, dy, dsum, apart(last), s)) return rc;
       for (int j = last; j >= 1; --j) {
         const void* in_j = w + u.conv[j - 1].a;
         if (int rc = conv_wgrad(b.convs[j], in_j, dy, wpart(j), static_cast<float*>(grad_ptrs[b.convs[j].w]), fork(s))) return rc;
         reader[dy_slot] = mark();
         const int next_slot = (dy_slot + 1) % 3;
-        void* dy_next = w + p.g[kDySlots[next_slot]];
+        void* dy_next = dy_slots[next_slot];
         if (int rc = wait_mark(s, reader[next_slot])) return rc;   // whoever read that slot is done with it
         reader[next_slot] = -1;
         // the gradient at convolution j's input only feeds the affine + ReLU below: one pass where the product can take it
@@ -465,7 +488,7 @@ class ResnetModel : public Model {
         dy_slot = next_slot;
       }
       const void* shortcut_grad = dsum;
-      void* dys = w + p.g[half ? 12 : 6];
+      void* dys = G(set, 3);
       if (b.has_proj)
         if (int rc = affine_bwd(b.proj, dsum, nullptr, w + u.proj.y, dys, nullptr, apart(kProjSlot), s)) return rc;
       {
@@ -480,29 +503,46 @@ class ResnetModel : public Model {
       }
       if (b.has_proj) {
         if (need_dx) {
-          if (int rc = conv_dgrad(b.proj, dys, param_ptrs[b.proj.w], nullptr, w + p.g[7], s)) return rc;
-          shortcut_grad = w + p.g[7];
+          if (int rc = conv_dgrad(b.proj, dys, param_ptrs[b.proj.w], nullptr, w + p.g[3], s)) return rc;
+          shortcut_grad = w + p.g[3];
         }
       }
       if (!need_dx) return SPB_OK;  // lowest unit: no input gradient
-      void* dx = w + p.g[dout_slot ^ 1];
-      if (int rc = conv_dgrad(b.convs[0], dy, param_ptrs[b.convs[0].w], shortcut_grad, dx, s)) return rc;
-      dout = dx;
-      dout_slot ^= 1;
+      if (fuses_into_unit_below(i)) {
+        // The unit's input gradient (this product plus the shortcut's) only feeds the affine + ReLU at the output of the
+        // unit below and, masked, that unit's shortcut: the product's epilogue does that pass and writes the unit
+        // below's first dy and its masked output gradient straight into that unit's set of buffers.
+        const Block& below = blocks_[i - 1];
+        const int set_below = (i - 1) % Plan::kSets, last_below = (int)below.convs.size() - 1;
+        if (i + 2 < (int)blocks_.size())
+          if (int rc = wait_mark(s, unit_done[i + 2])) return rc;   // the unit that last used that set
+        const int fused = conv_dgrad_affine(b.convs[0], dy, param_ptrs[b.convs[0].w], below.convs[last_below], x_in, w + p.unit[i].conv[last_below].y,
+                                            G(set_below, 0), apart_of(set_below, last_below), s, shortcut_grad, G(set_below, 4));
+        if (fused < 0) return fused;
+        if (fused > 0) { set_error("resnet: the last input gradient of unit %d cannot carry the affine pass below it", i + 1); return SPB_ERR_INVALID_ARG; }
+        incoming_fused = true;
+      } else {
+        void* dx = w + p.g[dout_slot ^ 1];
+        if (int rc = conv_dgrad(b.convs[0], dy, param_ptrs[b.convs[0].w], shortcut_grad, dx, s)) return rc;
+        dout = dx;
+        dout_slot ^= 1;
+        incoming_fused = false;
+      }
     }
     // ---- stem (unit 0), reached only at full depth ----
     if (cut == 0) {
-      if (int rc = join(s)) return rc;   // slot 3 is written next
+      if (int rc = join(s)) return rc;   // the buffers of set 0 are written next
       const UnitBuf& su = p.unit[0];
       const void* d = dout;
       if (pool_) {
         if (int rc = run("maxpool_bwd", (double)stem_.out_rows(batch_) * stem_.cout * 2 * 1.5, s, [&] {
-              return launch_maxpool_bwd(dout, reinterpret_cast<const uint8_t*>(w + su.which), w + p.g[4], batch_, stem_.out_h, stem_.out_w, stem_.cout, s); })) return rc;
-        d = w + p.g[4];
+              return launch_maxpool_bwd(dout, reinterpret_cast<const uint8_t*>(w + su.which), w + p.g[2], batch_, stem_.out_h, stem_.out_w, stem_.cout, s); })) return rc;
+        d = w + p.g[2];
       }
-      if (int rc = affine_bwd(stem_, d, w + su.conv[0].a, w + su.conv[0].y, w + p.g[3], nullptr, apart(0), s)) return rc;
+      set = 0;
+      if (int rc = affine_bwd(stem_, d, w + su.conv[0].a, w + su.conv[0].y, G(0, 0), nullptr, apart(0), s)) return rc;
       const void* stem_in = stem_.cin_eff != stem_.cin ? (const void*)(w + su.xpad) : x_;
-      if (int rc = conv_wgrad(stem_, stem_in, w + p.g[3], wpart(0), static_cast<float*>(grad_ptrs[stem_.w]), s)) return rc;
+      if (int rc = conv_wgrad(stem_, stem_in, G(0, 0), wpart(0), static_cast<float*>(grad_ptrs[stem_.w]), s)) return rc;
       if (int rc = flush_reduces(s)) return rc;
     }
     return SPB_OK;
@@ -520,16 +560,26 @@ class ResnetModel : public Model {
     } else {
       *input = make_view((long long)p.unit[nb].out, (long long)batch_ * final_h_ * final_w_, features_, features_, dtype);
     }
-    // The gradient entering the top block lies in slot 0 and the slots alternate from block to block.
+    // The gradient entering the top block lies in slot 0.  Below it, a unit whose upper neighbour fuses the output
+    // affine pass (the usual case) receives its gradient already masked by its own ReLU, in its set's fifth buffer;
+    // otherwise slots 0 and 1 alternate, as they do for the stem.
     if (unit == nb + 1 || k < 2) {
       *output_grad = no_view();
-    } else if (unit >= 1) {
-      const Conv& c = blocks_[unit - 1].convs.back();
-      *output_grad = make_view((long long)p.g[(nb - unit) & 1], c.out_rows(batch_), c.cout, c.cout, dtype);
-    } else {
-      const long long rows = pool_ ? (long long)batch_ * pool_h_ * pool_w_ : stem_.out_rows(batch_);
-      *output_grad = make_view((long long)p.g[nb & 1], rows, stem_.cout, stem_.cout, dtype);
+      return;
     }
+    int slot = 0;   // where an unfused hand-over lands next
+    for (int i = nb - 1; i >= 0; --i) {   // block i = unit i + 1, walked as the backward pass walks them
+      const bool fused_in = i < nb - 1 && fuses_into_unit_below(i + 1);
+      if (unit == i + 1) {
+        const Conv& c = blocks_[i].convs.back();
+        if (fused_in) *output_grad = make_view((long long)p.g[Plan::kSetBase + (i % Plan::kSets) * Plan::kPerSet + 4], c.out_rows(batch_), c.cout, c.cout, dtype, 1);
+        else *output_grad = make_view((long long)p.g[slot], c.out_rows(batch_), c.cout, c.cout, dtype);
+        return;
+      }
+      if (!fuses_into_unit_below(i)) slot ^= 1;   // this block writes its input gradient into the other slot
+    }
+    const long long rows = pool_ ? (long long)batch_ * pool_h_ * pool_w_ : stem_.out_rows(batch_);
+    *output_grad = make_view((long long)p.g[slot], rows, stem_.cout, stem_.cout, dtype);
   }
 
  private:
