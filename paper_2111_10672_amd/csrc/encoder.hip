@@ -58,7 +58,7 @@ class EncoderModel : public Model {
     std::vector<size_t> xout;        // output of unit u, u = 0..NL
     std::vector<LayerBuf> layer;     // per layer: own stash or the shared scratch
     size_t scores, y, statsf, logits, row_loss, dlogits;
-    size_t dy, partial, dx[2], dF[2], dv, dh[2], dctx, dscore, dqkv[2], du;
+    size_t dy, partial, partial_bytes, dx[2], dF[2], dv, dh[2], dctx, dscore, dqkv[2], du;
     size_t total;
   };
 
@@ -83,10 +83,12 @@ class EncoderModel : public Model {
     p.scores = take(zss * 4);
     p.y = take((size_t)R * H * 2); p.statsf = take((size_t)R * 8); p.logits = take((size_t)R * ldz() * 4);
     p.row_loss = take((size_t)R * 4); p.dlogits = take((size_t)R * ldv() * 2);
-    p.dy = p.partial = p.dx[0] = p.dx[1] = p.dF[0] = p.dF[1] = p.dv = p.dh[0] = p.dh[1] = p.dctx = p.dscore = p.dqkv[0] = p.dqkv[1] = p.du = 0;
+    p.dy = p.partial = p.partial_bytes = p.dx[0] = p.dx[1] = p.dF[0] = p.dF[1] = p.dv = p.dh[0] = p.dh[1] = p.dctx = p.dscore = p.dqkv[0] = p.dqkv[1] = p.du = 0;
     if (k >= 1) {
       p.dy = take((size_t)R * H * 2);
-      p.partial = take(std::max(layernorm_partial_floats(M, H), layernorm_partial_floats(R, H)) * 4);
+      // one per LayerNorm in the backward pass: their column sums are added up in one launch at the end
+      p.partial_bytes = align_up(std::max(layernorm_partial_floats(M, H), layernorm_partial_floats(R, H)) * 4, 256);
+      p.partial = take(p.partial_bytes * (size_t)(2 * std::min(k - 1, NL) + 1));
     }
     if (k >= 2) {
       // dF, dh and dqkv are read by weight gradients on the second stream: two of each, used by alternate layers
@@ -211,7 +213,15 @@ class EncoderModel : public Model {
     const int cut = num_units - k;
     const float inv_sqrt_d = 1.f / std::sqrt((float)D);
     const double mh = (double)M * H * 2;
-    float* partial = reinterpret_cast<float*>(w + p.partial);
+    // The column sums of every LayerNorm backward (dgamma, dbeta) are small reductions that feed nothing in this pass:
+    // each leaves its partial sums in a buffer of its own and one launch at the end adds all of them up, instead of
+    // two short kernels per layer on the chain.
+    std::vector<ReduceTask> ln_sums;
+    ln_sums.reserve(2 * NL + 1);
+    auto next_partial = [&]() {
+      ln_sums.emplace_back();
+      return reinterpret_cast<float*>(w + p.partial + p.partial_bytes * (ln_sums.size() - 1));
+    };
     auto G = [&](int idx) { return static_cast<float*>(grad_ptrs[idx]); };
 
     // ---- head (unit NL + 1) ----
@@ -239,9 +249,10 @@ class EncoderModel : public Model {
       dout = w + p.dx[0];
       if (int rc = run("fill_zero", mh, s, [&] { return launch_fill_zero(dout, (size_t)M * H * 2, s); })) return rc;
     }
+    float* part = next_partial();
     if (int rc = run("layernorm_bwd", 6.0 * R * H, s, [&] {
           return launch_layernorm_bwd(w + p.dy, H, w + p.xout[NL], H, rows_, reinterpret_cast<const float*>(w + p.statsf), param_ptrs[hp(0)],
-                                      nullptr, 0, dout, H, partial, G(hp(0)), G(hp(1)), R, H, s); })) return rc;
+                                      nullptr, 0, dout, H, part, G(hp(0)), G(hp(1)), R, H, s, &ln_sums.back()); })) return rc;
     int which = 0;  // dout lives in p.dx[which]
     std::vector<int> ffn_done(NL, -1), side_done(NL, -1);   // marks on the second stream: after a layer's first / second pair of weight gradients
 
@@ -274,9 +285,10 @@ class EncoderModel : public Model {
         ffn_done[i] = mark();
       }
       if (int rc = gemm(dgrad(dF, F, M, P(W1W), F, H, w + p.dv, H), s)) return rc;
+      part = next_partial();
       if (int rc = run("layernorm_bwd", 4 * mh, s, [&] {   // dh = dout + LN2 backward
             return launch_layernorm_bwd(w + p.dv, H, w + b.h, H, nullptr, reinterpret_cast<const float*>(w + b.stats2), P(LN2W), dout, H,
-                                        dh, H, partial, GP(LN2W), GP(LN2B), M, H, s); })) return rc;
+                                        dh, H, part, GP(LN2W), GP(LN2B), M, H, s, &ln_sums.back()); })) return rc;
       // attention half
       if (int rc = gemm(dgrad(dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
       const char* qbase = w + b.qkv;
@@ -324,13 +336,19 @@ class EncoderModel : public Model {
       // dx lands where the layer above found its incoming gradient, which that layer's feed-forward weight gradient reads
       if (dx && i + 1 < NL)
         if (int rc = wait_mark(s, ffn_done[i + 1])) return rc;
+      part = next_partial();
       if (int rc = run("layernorm_bwd", (lowest ? 2 : 4) * mh, s, [&] {   // dx = dh + LN1 backward; the lowest unit forms no input gradient
             return launch_layernorm_bwd(w + p.du, H, xin, H, nullptr, reinterpret_cast<const float*>(w + b.stats1), P(LN1W), dh, H,
-                                        dx, H, partial, GP(LN1W), GP(LN1B), M, H, s); })) return rc;
+                                        dx, H, part, GP(LN1W), GP(LN1B), M, H, s, &ln_sums.back()); })) return rc;
       if (lowest)
         if (int rc = gemm(wgrad(dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), s)) return rc;
       dout = dx;
       which ^= 1;
+    }
+    {
+      double bytes = 0;
+      for (const ReduceTask& t : ln_sums) bytes += (double)(t.count + 1) * 2 * t.width * 4;
+      if (int rc = run("layernorm_sums", bytes, s, [&] { return launch_unit_reduce(ln_sums.data(), (int)ln_sums.size(), s); })) return rc;
     }
     // ---- embedding (unit 0), only at full depth ----
     if (cut == 0)

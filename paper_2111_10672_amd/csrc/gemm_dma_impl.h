@@ -1465,6 +1465,13 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
   // 128 x 128: two workgroups per CU hide each other's barriers when there are tiles for that; a workgroup
   // alone on its CU keeps three tiles in flight instead (a four-stage ring; a fifth stage measured slower).
   if (tiles(128, 128) > 256) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);
+  // Weight gradients of the encoder's dense layers (K = tokens): 108-144 tiles of 128 x 128.  Alone on the chip that
+  // is level with 576 tiles of 64 x 64, but these products run beside the input-gradient chain of the other stream,
+  // and there the big tiles do the same work in half the CU time and leave the other CUs to that chain (+5 % on the
+  // encoder step; the four-wave kernels with two or three stages gave +1 and +3 %).
+  if constexpr (LA == Layout::KRow && LB == Layout::KRow && GA == Gather::None && GB == Gather::None) {
+    if (tiles(128, 128) >= 96 && q.K >= 2048) return launch_tile_pipe<128, 128, 4, 2, 4, 2, LA, LB, GA, GB>(q, stream);
+  }
   if (tiles(128, 128) >= 192) {
     // one round of lone workgroups: convolutions (gathered operands) did 2-5 % better as two 128 x 64 workgroups per
     // CU; plain products were level, and 128 x 128 leaves LDS for a weight-gradient workgroup of the second stream

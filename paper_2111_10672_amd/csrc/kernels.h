@@ -164,7 +164,7 @@ struct ReduceTask {
   unsigned blocks = 0;
 };
 struct ReduceTable {
-  static constexpr int kMax = 8;
+  static constexpr int kMax = 32;
   int n = 0;
   unsigned end_block[kMax] = {};
   ReduceTask task[kMax];
@@ -198,11 +198,12 @@ hipError_t launch_layernorm_fwd(const void* x, int ldx, const int32_t* rows, int
                                 void* y, int ldy, float* stats, hipStream_t s);
 // LayerNorm backward.  dy and stats are indexed by r, x and dx by rows ? rows[r] : r.  dx (optional) receives the input
 // gradient plus res[r] (optional).  dgamma/dbeta (float32 [width]) are overwritten; partial is scratch of
-// layernorm_partial_floats(n_rows, width) floats.
+// layernorm_partial_floats(n_rows, width) floats.  With `deferred` the column sums are not added up here: the task
+// describes that reduction for a later launch_unit_reduce, and `partial` must stay untouched until then.
 size_t layernorm_partial_floats(int n_rows, int width);
 hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx, const int32_t* rows, const float* stats,
                                 const void* gamma, const void* res, int ldres, void* dx, int lddx, float* partial,
-                                float* dgamma, float* dbeta, int n_rows, int width, hipStream_t s);
+                                float* dgamma, float* dbeta, int n_rows, int width, hipStream_t s, ReduceTask* deferred = nullptr);
 // prob (bfloat16) = softmax of each row of scores (float32), rows of `len` contiguous entries.
 hipError_t launch_softmax_fwd(const float* scores, void* prob, long long n_rows, int len, hipStream_t s);
 // dscore (bfloat16) = prob * (dprob - sum(dprob * prob)) * scale per row.

@@ -501,7 +501,7 @@ hipError_t launch_layernorm_fwd(const void* x, int ldx, const int32_t* rows, int
 
 hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx, const int32_t* rows, const float* stats,
                                 const void* gamma, const void* res, int ldres, void* dx, int lddx, float* partial,
-                                float* dgamma, float* dbeta, int n_rows, int width, hipStream_t s) {
+                                float* dgamma, float* dbeta, int n_rows, int width, hipStream_t s, ReduceTask* deferred) {
   if (!dy || !x || !stats || !gamma || !partial || !dgamma || !dbeta || n_rows <= 0) return hipErrorInvalidValue;
   if (!row_ok(width, lddy) || !row_ok(width, ldx) || (dx && !row_ok(width, lddx)) || (res && !row_ok(width, ldres))) return hipErrorInvalidValue;
   if (!a16(dy) || !a16(x) || !a16(gamma) || !a16(dx) || !a16(res)) return hipErrorInvalidValue;
@@ -528,6 +528,11 @@ hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (deferred) {   // the caller adds the column sums up later, several layers' in one launch
+    deferred->kind = ReduceTask::kPairs; deferred->partial = partial; deferred->count = blocks; deferred->width = width;
+    deferred->out = dgamma; deferred->out_b = dbeta; deferred->blocks = (unsigned)((2 * width + 3) / 4);
+    return hipSuccess;
+  }
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 15) / 16), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
   return hipGetLastError();
 }
