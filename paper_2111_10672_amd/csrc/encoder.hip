@@ -290,7 +290,14 @@ class EncoderModel : public Model {
             return launch_layernorm_bwd(w + p.dv, H, w + b.h, H, nullptr, reinterpret_cast<const float*>(w + b.stats2), P(LN2W), dout, H,
                                         dh, H, part, GP(LN2W), GP(LN2B), M, H, s, &ln_sums.back()); })) return rc;
       // attention half
-      if (int rc = gemm(dgrad(dh, H, M, P(OUTW), H, H, w + p.dctx, H), s)) return rc;
+      // (this product and the one through Wqkv run beside the feed-forward weight gradients, whose workgroups take
+      // 128 KB of a CU's LDS: with 64 KB tiles of their own they find room on the same CUs - +2 % on the step; the
+      // product through W1 measured better with the big-footprint kernel)
+      {
+        GemmProblem g = dgrad(dh, H, M, P(OUTW), H, H, w + p.dctx, H);
+        g.share_cu = true;
+        if (int rc = gemm(g, s)) return rc;
+      }
       const char* qbase = w + b.qkv;
       if (attention_fused_accepts(S, D, 3 * H, H)) {
         if (int rc = run("attention_bwd", (double)M * H * 2 * 7 + (double)Z * S * S * 2, s, [&] {
@@ -331,7 +338,11 @@ class EncoderModel : public Model {
           if (int rc = gemm(wgrad(dqkv, 3 * H, w + b.u, H, M, 3 * H, H, GP(QKVW), GP(QKVB)), side)) return rc;
         side_done[i] = mark();
       }
-      if (int rc = gemm(dgrad(dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H), s)) return rc;
+      {
+        GemmProblem g = dgrad(dqkv, 3 * H, M, P(QKVW), 3 * H, H, w + p.du, H);
+        g.share_cu = true;
+        if (int rc = gemm(g, s)) return rc;
+      }
       void* dx = lowest ? nullptr : w + p.dx[which ^ 1];
       // dx lands where the layer above found its incoming gradient, which that layer's feed-forward weight gradient reads
       if (dx && i + 1 < NL)

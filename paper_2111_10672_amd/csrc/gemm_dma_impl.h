@@ -1476,6 +1476,7 @@ hipError_t launch_layouts(const GemmProblem& q, hipStream_t stream) {
     // one round of lone workgroups: convolutions (gathered operands) did 2-5 % better as two 128 x 64 workgroups per
     // CU; plain products were level, and 128 x 128 leaves LDS for a weight-gradient workgroup of the second stream
     if constexpr (GA != Gather::None || GB != Gather::None) return launch_tile<128, 64, 3, 4, 1, LA, LB, GA, GB>(q, stream);
+    else if (q.share_cu) return launch_tile<128, 128, 2, 2, 2, LA, LB, GA, GB>(q, stream);   // 64 KB of LDS instead of 128
     else return launch_tile_pipe<128, 128, 4, 2, 4, 2, LA, LB, GA, GB>(q, stream);   // eight waves: a lone workgroup needs two per SIMD to hide its own latencies
   }
   // 64 x 64: the ring depth that lets every tile be resident at once (two or three workgroups per CU).

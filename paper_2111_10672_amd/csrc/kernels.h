@@ -87,6 +87,9 @@ struct GemmProblem {
   // The buffer's owner keeps zeros between the end of each row's data and the next multiple of 8 elements
   // along the contiguous index (lets a kernel fetch whole 16-byte chunks).
   bool a_pad_zero = false, b_pad_zero = false;
+  // The product runs beside workgroups of another stream: where the tile choice is between one 128 x 128 workgroup
+  // that takes most of a CU's LDS and one that leaves room for a neighbour, take the latter.
+  bool share_cu = false;
   float* a_row_sum = nullptr;     // optional [M]: sum_k A(m, k), written once by the tiles of column block 0
   // AffineBwdStore: the affine's input (pre-affine convolution output), the partial column sums [tile rows][2][N]
   // (room for (M + 63) / 64 tile rows) and where the launcher reports how many tile rows it wrote
