@@ -108,19 +108,28 @@ __global__ __launch_bounds__(256) void affine_relu_bwd_kernel(const uint16_t* __
   }
 }
 
-// out_a[c] = sum_b partial[b][0][c], out_b[c] = sum_b partial[b][1][c].  One wavefront per column: lane l adds blocks
-// l, l + 64, ... in order, then the 64 lane sums are combined by a fixed shuffle tree (same bits on every run).
+// out_a[c] = sum_b partial[b][0][c], out_b[c] = sum_b partial[b][1][c].  A workgroup takes 16 neighbouring columns
+// (reduce_pairs_blocks workgroups in all): thread (g, c) adds blocks g, g + 16, ... of column c in order - the 16
+// threads of a group read 64 contiguous bytes, where one wavefront per column touched a cache line per lane - and
+// the 16 group sums of a column are added in group order: the same bits on every run.
 __device__ __forceinline__ void reduce_pairs_block(unsigned block, const float* __restrict__ partial, int n_blocks, int width,
                                                    float* __restrict__ out_a, float* __restrict__ out_b) {
-  const int lane = threadIdx.x & 63, col = block * 4 + (threadIdx.x >> 6);
-  if (col >= 2 * width) return;
+  __shared__ float sh[16][17];
+  const int c = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int col = block * 16 + c;
   float s = 0.f;
-  for (int b = lane; b < n_blocks; b += 64) s += partial[(size_t)b * 2 * width + col];
+  if (col < 2 * width) {
+#pragma unroll 8
+    for (int b = g; b < n_blocks; b += 16) s += partial[(size_t)b * 2 * width + col];
+  }
+  sh[g][c] = s;
+  __syncthreads();
+  if (threadIdx.x < 16 && col < 2 * width) {
+    float t = 0.f;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-  if (lane == 0) {
-    if (col < width) out_a[col] = s;
-    else out_b[col - width] = s;
+    for (int q = 0; q < 16; ++q) t += sh[q][c];
+    if (col < width) out_a[col] = t;
+    else out_b[col - width] = t;
   }
 }
 __global__ __launch_bounds__(256) void reduce_pairs_kernel(const float* __restrict__ partial, int n_blocks, int width,
@@ -341,10 +350,10 @@ hipError_t launch_affine_relu_bwd(const void* dout, const void* act, const void*
   if (e != hipSuccess) return e;
   if (deferred) {   // the caller adds the column sums up later (launch_unit_reduce)
     deferred->kind = ReduceTask::kPairs; deferred->partial = partial; deferred->count = blocks; deferred->width = channels;
-    deferred->out = dscale; deferred->out_b = dshift; deferred->blocks = (unsigned)((2 * channels + 3) / 4);
+    deferred->out = dscale; deferred->out_b = dshift; deferred->blocks = reduce_pairs_blocks(channels);
     return hipSuccess;
   }
-  hipLaunchKernelGGL(reduce_pairs_kernel, dim3((2 * channels + 3) / 4), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
+  hipLaunchKernelGGL(reduce_pairs_kernel, dim3(reduce_pairs_blocks(channels)), dim3(256), 0, s, partial, blocks, channels, dscale, dshift);
   return hipGetLastError();
 }
 

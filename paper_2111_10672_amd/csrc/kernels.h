@@ -166,6 +166,7 @@ struct ReduceTask {
   int cin = 0, cin_padded = 0;
   unsigned blocks = 0;
 };
+inline unsigned reduce_pairs_blocks(int width) { return (unsigned)((2 * width + 15) / 16); }   // workgroups of a kPairs task
 struct ReduceTable {
   static constexpr int kMax = 32;
   int n = 0;

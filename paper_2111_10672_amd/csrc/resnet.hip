@@ -302,7 +302,7 @@ class ResnetModel : public Model {
     const int tile_rows = fused_tile_rows_;
     task.kind = ReduceTask::kPairs; task.partial = partial; task.count = tile_rows; task.width = below.cout;
     task.out = static_cast<float*>(grad_ptrs[below.scale]); task.out_b = static_cast<float*>(grad_ptrs[below.shift]);
-    task.blocks = (unsigned)((2 * below.cout + 3) / 4);
+    task.blocks = reduce_pairs_blocks(below.cout);
     reduce_bytes_ += (double)tile_rows * 2 * below.cout * 4;
     reduces_.push_back(task);
     return SPB_OK;

@@ -530,7 +530,7 @@ hipError_t launch_layernorm_bwd(const void* dy, int lddy, const void* x, int ldx
   if (e != hipSuccess) return e;
   if (deferred) {   // the caller adds the column sums up later, several layers' in one launch
     deferred->kind = ReduceTask::kPairs; deferred->partial = partial; deferred->count = blocks; deferred->width = width;
-    deferred->out = dgamma; deferred->out_b = dbeta; deferred->blocks = (unsigned)((2 * width + 3) / 4);
+    deferred->out = dgamma; deferred->out_b = dbeta; deferred->blocks = reduce_pairs_blocks(width);
     return hipSuccess;
   }
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((2 * width + 15) / 16), dim3(256), 0, s, partial, blocks, width, dgamma, dbeta);
