@@ -141,7 +141,10 @@ class ResnetModel : public Model {
   int wgrad_splits(const Conv& c) const {
     const long tiles = (long)((c.cout + 127) / 128) * ((c.k_total() + 127) / 128);
     const long k_tiles = (long)((c.out_rows(batch_) + 63) / 64);
-    long s = (256 + tiles - 1) / tiles;
+    // k-slices for about 192 workgroups, not one per CU: the weight gradients run beside the input-gradient chain of the
+    // other stream, and a quarter of the CUs left to that chain measured best on the step (128: -0.6 %, 256: -1.1 to
+    // -1.8 %, 512: -3.5 to -8 %)
+    long s = (192 + tiles - 1) / tiles;
     s = std::min(s, std::max(1L, k_tiles / 4));
     return (int)std::max(1L, std::min(s, 1024L));
   }
