@@ -644,7 +644,9 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
   // math(v, x, pre): v = alpha * acc on entry and the result on return; x = the per-element tensor's 8 values (only
   // with has_x); pre = what the auxiliary output stores (only worked out with has_aux).  Both flags are template
   // arguments of the variant so that a product without those tensors spends no instruction on them.
-  auto run = [&](auto has_x, auto has_aux, auto&& math) {
+  // (always_inline: for large wave tiles the inliner otherwise leaves this body a function, and the accumulators,
+  // passed by reference, then live in scratch memory through the whole tile loop)
+  auto run = [&](auto has_x, auto has_aux, auto&& math) __attribute__((always_inline)) {
     constexpr bool kX = decltype(has_x)::value, kAux = decltype(has_aux)::value;
     u32x4 xs[2][kIters];
     if constexpr (kX) request(0, xs[0]);
@@ -820,7 +822,7 @@ __device__ __forceinline__ void store_wave_tile(const GemmParams& p, f32x16 (&ac
     }
   };
   // the four combinations of (residual, auxiliary output) of one activation
-  auto variants = [&](auto&& math) {
+  auto variants = [&](auto&& math) __attribute__((always_inline)) {
     if (xsrc != nullptr) {
       if (aux != nullptr) run(Yes{}, Yes{}, math);
       else run(Yes{}, No{}, math);
