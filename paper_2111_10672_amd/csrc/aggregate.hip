@@ -14,7 +14,8 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxTensors = 24;
-constexpr int kChunkElems = 2048;  // elements per workgroup: 256 threads x 2 x 4
+constexpr int kParts = 2;                        // 4-element pieces per thread
+constexpr int kChunkElems = 256 * kParts * 4;    // elements per workgroup
 
 struct AggTensor {
   void* w;                         // parameter, model dtype
@@ -24,6 +25,7 @@ struct AggTensor {
   int first_block;                 // first workgroup of this tensor in the launch
   int count;                       // contributors
   float rate;                      // learning rate of this tensor
+  int aligned;                     // numel % 4 == 0 and every buffer 16-byte aligned: the vector path
 };
 struct AggTable {
   AggTensor t[kMaxTensors];
@@ -35,6 +37,50 @@ struct AggTable {
 __device__ __forceinline__ float bf(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
 __device__ __forceinline__ uint16_t to_bf16(float v) { return bf16_round(v); }
 
+// The common case (element count a multiple of 4, every buffer 16-byte aligned): a thread's kParts 4-element pieces, all
+// of their C + 2 loads requested before the first is used, parameters as one 8- or 16-byte access per piece.  The
+// additions run in worker order, as in the general path below: same bits.
+template <int C>
+__device__ __forceinline__ void update_aligned(const AggTensor& t, const AggTable& tab, long long base) {
+  f32x4 x[kParts][C], vv[kParts], ww[kParts];
+  uint2 wb[kParts];
+  long long e0[kParts];
+  bool live[kParts];
+#pragma unroll
+  for (int part = 0; part < kParts; ++part) {
+    e0[part] = base + (long long)(part * 256 + threadIdx.x) * 4;
+    live[part] = e0[part] < t.numel;
+    if (!live[part]) continue;
+#pragma unroll
+    for (int j = 0; j < C; ++j) x[part][j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(t.g[j] + e0[part]));   // read once
+    vv[part] = *reinterpret_cast<const f32x4*>(t.v + e0[part]);
+    if (tab.bf16) wb[part] = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(t.w) + e0[part]);
+    else ww[part] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(t.w) + e0[part]);
+  }
+  const float inv = 1.f / (float)C;
+#pragma unroll
+  for (int part = 0; part < kParts; ++part) {
+    if (!live[part]) continue;
+    f32x4 g = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < C; ++j) g += x[part][j];   // workers added in index order
+    f32x4 w = ww[part];
+    if (tab.bf16) w = f32x4{__uint_as_float(wb[part].x << 16), __uint_as_float(wb[part].x & 0xFFFF0000u),
+                            __uint_as_float(wb[part].y << 16), __uint_as_float(wb[part].y & 0xFFFF0000u)};
+    f32x4 v = vv[part];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] = tab.momentum * v[e] + (g[e] * inv + tab.weight_decay * w[e]);
+      w[e] = w[e] - t.rate * v[e];
+    }
+    *reinterpret_cast<f32x4*>(t.v + e0[part]) = v;
+    if (tab.bf16)
+      *reinterpret_cast<uint2*>(static_cast<uint16_t*>(t.w) + e0[part]) =
+          uint2{(uint32_t)to_bf16(w[0]) | ((uint32_t)to_bf16(w[1]) << 16), (uint32_t)to_bf16(w[2]) | ((uint32_t)to_bf16(w[3]) << 16)};
+    else *reinterpret_cast<f32x4*>(static_cast<float*>(t.w) + e0[part]) = w;
+  }
+}
+
 __global__ __launch_bounds__(256) void aggregate_update_kernel(AggTable tab) {
   // which tensor: the last one whose first_block is not past this workgroup (uniform, a handful of compares)
   int ti = 0;
@@ -42,34 +88,36 @@ __global__ __launch_bounds__(256) void aggregate_update_kernel(AggTable tab) {
     if ((int)blockIdx.x >= tab.t[i].first_block) ti = i;
   const AggTensor& t = tab.t[ti];
   const long long base = (long long)((int)blockIdx.x - t.first_block) * kChunkElems;
+  if (t.aligned) {   // uniform over the workgroup
+    switch (t.count) {
+      case 1: update_aligned<1>(t, tab, base); return;
+      case 2: update_aligned<2>(t, tab, base); return;
+      case 3: update_aligned<3>(t, tab, base); return;
+      case 4: update_aligned<4>(t, tab, base); return;
+      case 5: update_aligned<5>(t, tab, base); return;
+      case 6: update_aligned<6>(t, tab, base); return;
+      case 7: update_aligned<7>(t, tab, base); return;
+      case 8: update_aligned<8>(t, tab, base); return;
+      default: break;
+    }
+  }
   const float inv = 1.f / (float)t.count;
-  const bool vec = (t.numel & 3) == 0;
 #pragma unroll
-  for (int part = 0; part < 2; ++part) {
+  for (int part = 0; part < kParts; ++part) {
     const long long e0 = base + (long long)(part * 256 + threadIdx.x) * 4;
     if (e0 >= t.numel) continue;
     float g[4] = {0.f, 0.f, 0.f, 0.f}, w[4], v[4];
     const int live = (int)(t.numel - e0 < 4 ? t.numel - e0 : 4);
-    if (vec) {
-      for (int j = 0; j < t.count; ++j) {   // workers added in index order
-        const f32x4 x = *reinterpret_cast<const f32x4*>(t.g[j] + e0);
-        g[0] += x[0]; g[1] += x[1]; g[2] += x[2]; g[3] += x[3];
-      }
-      const f32x4 vv = *reinterpret_cast<const f32x4*>(t.v + e0);
-      v[0] = vv[0]; v[1] = vv[1]; v[2] = vv[2]; v[3] = vv[3];
-    } else {
-      for (int j = 0; j < t.count; ++j)
-        for (int e = 0; e < live; ++e) g[e] += t.g[j][e0 + e];
-      for (int e = 0; e < live; ++e) v[e] = t.v[e0 + e];
-    }
+    for (int j = 0; j < t.count; ++j)   // workers added in index order
+      for (int e = 0; e < live; ++e) g[e] += t.g[j][e0 + e];
+    for (int e = 0; e < live; ++e) v[e] = t.v[e0 + e];
     for (int e = 0; e < live; ++e)
       w[e] = tab.bf16 ? bf(static_cast<const uint16_t*>(t.w)[e0 + e]) : static_cast<const float*>(t.w)[e0 + e];
     for (int e = 0; e < live; ++e) {
       v[e] = tab.momentum * v[e] + (g[e] * inv + tab.weight_decay * w[e]);
       w[e] = w[e] - t.rate * v[e];
     }
-    if (vec) *reinterpret_cast<f32x4*>(t.v + e0) = f32x4{v[0], v[1], v[2], v[3]};
-    else for (int e = 0; e < live; ++e) t.v[e0 + e] = v[e];
+    for (int e = 0; e < live; ++e) t.v[e0 + e] = v[e];
     for (int e = 0; e < live; ++e) {
       if (tab.bf16) static_cast<uint16_t*>(t.w)[e0 + e] = to_bf16(w[e]);
       else static_cast<float*>(t.w)[e0 + e] = w[e];
@@ -92,10 +140,13 @@ hipError_t launch_aggregate_update(const AggregateTensor* tensors, int n_tensors
       if (!s.w || !s.v || s.numel <= 0 || s.count < 1 || s.count > kMaxAggWorkers) return hipErrorInvalidValue;
       AggTensor& d = tab.t[tab.n++];
       d.w = s.w; d.v = s.v; d.numel = s.numel; d.count = s.count; d.rate = s.rate; d.first_block = blocks;
+      uintptr_t bits = reinterpret_cast<uintptr_t>(s.w) | reinterpret_cast<uintptr_t>(s.v) | (uintptr_t)(s.numel & 3);
       for (int j = 0; j < s.count; ++j) {
         if (!s.g[j]) return hipErrorInvalidValue;
         d.g[j] = s.g[j];
+        bits |= reinterpret_cast<uintptr_t>(s.g[j]);
       }
+      d.aligned = (bits & 15) == 0;
       blocks += (int)((s.numel + kChunkElems - 1) / kChunkElems);
     }
     hipLaunchKernelGGL(aggregate_update_kernel, dim3(blocks), dim3(256), 0, stream, tab);
