@@ -873,7 +873,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   int tile_m, tile_n;
-  xcd_tile_grouped(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  xcd_tile_grouped(p.slice_in_x ? blockIdx.y : blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -881,7 +881,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_dma_kernel(G
 
   TileSource<BM, LA, GA, NW> src_a;
   TileSource<BN, LB, GB, NW> src_b;
-  const int z = blockIdx.y;  // batch entry, or slice of the k range
+  const int z = p.slice_in_x ? blockIdx.x : blockIdx.y;  // batch entry, or slice of the k range
   int t_first = 0, n_steps = (p.K + kTileK - 1) / kTileK;
   if (p.k_tiles_per_split > 0) {
     t_first = z * p.k_tiles_per_split;
@@ -1019,7 +1019,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
   static_assert((size_t)NW * 32 * (WN + 4) * 4 <= (size_t)STAGES * kStageBytes, "epilogue staging fits in the tile ring");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   int tile_m, tile_n;
-  xcd_tile_grouped(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  xcd_tile_grouped(p.slice_in_x ? blockIdx.y : blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1027,7 +1027,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void gemm_bf16_pipe_kernel(
 
   SourceA src_a;
   SourceB src_b;
-  const int z = blockIdx.y;  // batch entry, or slice of the k range
+  const int z = p.slice_in_x ? blockIdx.x : blockIdx.y;  // batch entry, or slice of the k range
   int t_first = 0, n_steps = (p.K + kTileK - 1) / kTileK;
   if (p.k_tiles_per_split > 0) {
     t_first = z * p.k_tiles_per_split;
@@ -1407,7 +1407,9 @@ hipError_t launch_tile(const GemmProblem& q, hipStream_t stream) {
   auto kernel = gemm_bf16_dma_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, LA, LB, GA, GB>;
   if (lds_bytes > 64 * 1024)
     if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes); e != hipSuccess) return e;
-  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  p.slice_in_x = q.k_splits > 1 && q.k_splits % 8 == 0 && p.tiles_m * p.tiles_n <= 65535;
+  const dim3 grid = p.slice_in_x ? dim3(grid_y, p.tiles_m * p.tiles_n) : dim3(p.tiles_m * p.tiles_n, grid_y);
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
@@ -1426,7 +1428,9 @@ hipError_t launch_tile_pipe(const GemmProblem& q, hipStream_t stream) {
   auto kernel = gemm_bf16_pipe_kernel<BM, BN, STAGES, WAVES_M, WAVES_N, KGB, LA, LB, GA, GB>;
   if (lds_bytes > 64 * 1024)
     if (hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kernel), lds_bytes); e != hipSuccess) return e;
-  hipLaunchKernelGGL(kernel, dim3(p.tiles_m * p.tiles_n, grid_y), dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
+  p.slice_in_x = q.k_splits > 1 && q.k_splits % 8 == 0 && p.tiles_m * p.tiles_n <= 65535;
+  const dim3 grid = p.slice_in_x ? dim3(grid_y, p.tiles_m * p.tiles_n) : dim3(p.tiles_m * p.tiles_n, grid_y);
+  hipLaunchKernelGGL(kernel, grid, dim3(64 * WAVES_M * WAVES_N), lds_bytes, stream, p);
   return hipGetLastError();
 }
 
